@@ -1,0 +1,183 @@
+#!/usr/bin/env python3
+"""Benchmark of the DPPF consensus round on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--call round|pull_push|local_step]
+
+One "step" is one pass of the whole hot path over one batch of synthetic input: the fused
+`dppf_round` (last local momentum-SGD step + replica average + distances + pull-push update)
+over the M resident replicas of a ViT-B/16-sized parameter list.  Inputs are generated on the
+host with the seeded recipe of `paper_2507_20424_amd.workloads`, uploaded once, and resident
+in HBM before the timed region starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
+# algorithmic HBM bytes per replica-parameter (fp32): what the method itself must move
+BYTES_PER_RP = {
+    "step_reduce": 20.0,        # read x, v, g; write x, v (average and distances ride along)
+    "reduce": 4.0,              # read x
+    "update": 8.0,              # read x, write x
+    "local_step": 20.0,         # read x, v, g; write x, v
+    "finalize": 0.0,
+}
+CALL_BYTES = {"round": 28.0, "pull_push": 12.0, "local_step": 20.0}
+
+
+def kernel_source_hash() -> str:
+    with open(os.path.join(ROOT, "paper_2507_20424_amd", "csrc", "dppf.hip"), "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
+
+
+def measured_traffic(kernel: str, workload: str):
+    """HBM bytes per launch from rocprofv3 counter runs, if they were taken on this very
+    kernel source; None otherwise."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        table = json.load(f)
+    if table.get("kernel_source_sha256_16") != kernel_source_hash():
+        return None
+    return table.get("bytes_per_launch", {}).get(f"{workload}:{kernel}")
+
+
+def cpu_baseline(spec, inp, g_host, hyper, sample_cols: int):
+    """The CPU oracle as it stands, timed on a bounded sample of the same workload: the first
+    `sample_cols` coordinates of every worker (one local step + one round, float64)."""
+    import numpy as np
+    from oracle import dppf_oracle as O
+    n = min(sample_cols, spec.d)
+    x = np.stack([a[:n] for a in inp.x])
+    v = np.stack([a[:n] for a in inp.v])
+    g = np.stack([a[:n] for a in g_host])
+    t0 = time.perf_counter()
+    O.dppf_round(x, v, g, hyper["lr"], hyper["mu"], hyper["wd"], hyper["pull"], hyper["push"])
+    dt = time.perf_counter() - t0
+    return {"value": spec.M * n / dt, "unit": "replica-params/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {n} of d={spec.d} coordinates of all M={spec.M} workers, one local step + one "
+                      f"round in float64 numpy, {dt:.1f} s"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="vitb16_M4")
+    ap.add_argument("--call", default="round", choices=sorted(CALL_BYTES))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-cols", type=int, default=40_000_000)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU (the M workers are M replicas resident in one GPU's "
+              "HBM); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2507_20424_amd import dppf, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    spec = W.SPECS[args.workload]
+    f32 = lambda a: float(np.float32(a))  # noqa: E731
+    hyper = dict(lr=f32(spec.lr), mu=f32(spec.momentum), wd=f32(spec.weight_decay), pull=f32(spec.pull),
+                 push=f32(spec.push))
+    inp = W.make_inputs(spec)
+    g_host = inp.grads(0)
+
+    def rows(arrays):     # one separately allocated device tensor per list entry, like a model's parameters
+        out = []
+        for a in arrays:
+            out.append([torch.from_numpy(a[inp.offsets[t]:inp.offsets[t + 1]]).to("cuda") for t in range(spec.T)])
+        return out
+
+    x, v, g = rows(inp.x), rows(inp.v), rows(g_host)
+    r = torch.zeros(spec.M, device="cuda")
+    c = torch.zeros(spec.M, device="cuda")
+    plan = dppf.Plan(spec.M, spec.numel)
+    xt, vt, gt = dppf.PointerTable(x), dppf.PointerTable(v), dppf.PointerTable(g)
+
+    def step():
+        if args.call == "round":
+            plan.round(xt, vt, gt, hyper["lr"], hyper["mu"], hyper["wd"], hyper["pull"], hyper["push"], r_out=r,
+                       c_out=c)
+        elif args.call == "pull_push":
+            plan.pull_push_round(xt, hyper["pull"], hyper["push"], r_out=r, c_out=c)
+        else:
+            plan.local_sgd_step(xt, vt, gt, hyper["lr"], hyper["mu"], hyper["wd"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    n_rp = spec.M * spec.d
+    value = n_rp / (dt / args.steps)
+
+    # per-kernel durations with HIP events on the launch stream, over the same number of steps
+    plan.timing_enable(True)
+    for _ in range(args.steps):
+        step()
+    recs = plan.timing_read(cap=8 * args.steps + 8)
+    plan.timing_enable(False)
+    per_kernel = {}
+    for name, ms in recs:
+        per_kernel.setdefault(name, []).append(ms)
+    avg_ms = {k: sum(vv) / len(vv) for k, vv in per_kernel.items()}
+    dominant = max(avg_ms, key=lambda k: avg_ms[k])
+    achieved = BYTES_PER_RP[dominant] * n_rp / (avg_ms[dominant] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(dominant, spec.name),
+                "avg_kernel_ms": avg_ms[dominant],
+                "algorithmic_bytes_per_launch": BYTES_PER_RP[dominant] * n_rp}
+    torch.cuda.synchronize()
+    assert torch.isfinite(r).all() and torch.isfinite(x[0][-1]).all()
+
+    out = {
+        "metric": "dppf_round_replica_params_per_s",
+        "value": value,
+        "unit": "replica-params/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": spec.name, "call": f"dppf_{args.call}", "M": spec.M, "d": spec.d, "T": spec.T,
+                   "replica_params": n_rp, "pull": hyper["pull"], "push": hyper["push"], "lr": hyper["lr"],
+                   "momentum": hyper["mu"], "weight_decay": hyper["wd"]},
+        "effective_GBps": CALL_BYTES[args.call] * value / 1e9,
+        "effective_frac_of_hbm_peak": CALL_BYTES[args.call] * value / 1e9 / HBM_PEAK_GBS,
+        "kernel_ms": avg_ms,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(spec, inp, g_host, hyper, args.cpu_sample_cols)
+    plan.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

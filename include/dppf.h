@@ -1,0 +1,142 @@
+/*
+ * dppf.h -- C ABI of the DPPF consensus-round library for AMD MI355X (gfx950).
+ *
+ * The library implements, for M workers whose fp32 parameter vectors x_1..x_M all live in
+ * the memory of ONE GPU, the consensus round of Distributed Pull-Push Force and the local
+ * optimizer step that runs between rounds:
+ *
+ *   x_A  = (1/M) sum_m x_m                              (Alg. 1, last line; Sec. 4)
+ *   r_m  = || x_m - x_A ||_2   over the WHOLE model     (Alg. 1, push line; Eq. 5)
+ *   x_m <- x_m + (x_A - x_m) * (alpha - lambda / r_m)   (Sec. 5, Eq. 5)
+ *   v_m <- mu v_m + (g_m + wd x_m);  x_m <- x_m - eta v_m   (Alg. 1, SGD line, with the
+ *                                     momentum 0.9 the experiments state in the appendix)
+ *
+ * Conventions common to every entry point
+ *  - A model is a list of T tensors; worker m's copy of tensor t has numel[t] fp32 elements.
+ *    The norm r_m runs over the concatenation of all T tensors.
+ *  - "Pointer table" arguments are HOST arrays of DEVICE pointers.  Per-worker tables hold
+ *    M*T entries, worker-major: table[m*T + t].  Per-model tables (x_A, x_C) hold T entries.
+ *    The library copies a table to a plan-owned device buffer the first time it sees it and
+ *    again only when its contents change; the host array may be freed after the call returns.
+ *  - Every tensor pointer must be 4-byte aligned; nothing more is required (no 16-byte
+ *    alignment, no padding, any numel >= 0).  Tensors must not overlap one another.
+ *  - All tensors are owned by the caller.  x and v (and the Adam moments) are updated IN
+ *    PLACE.  The library never allocates, frees or resizes caller memory.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *    ENQUEUE work on it and return without waiting for the GPU.  A plan must not be used
+ *    from two streams or two host threads at the same time (it owns scratch buffers).
+ *  - Small outputs r_out / c_out are DEVICE arrays of M floats, written by the enqueued work.
+ *  - Return value: DPPF_OK (0) or a negative DPPF_E* code.  No exceptions, no aborts.
+ *    Arguments are validated before anything is enqueued; on error nothing was launched.
+ *  - A worker at distance zero (r_m == 0, e.g. identical replicas) is NOT an error: the
+ *    direction of its push is undefined, its displacement is the zero vector, so its x_m is
+ *    left bit-for-bit unchanged, r_m = 0 and c_m = alpha are reported.
+ *  - pull (alpha) and push (lambda) are used as given: no clamping, no division by M.
+ */
+#ifndef DPPF_H_
+#define DPPF_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  DPPF_OK = 0,
+  DPPF_EINVAL = -1,  /* bad argument: null required pointer, M < 1, T < 0, numel < 0,
+                        misaligned tensor pointer, size mismatch with the plan            */
+  DPPF_EHIP = -2,    /* a HIP runtime call failed; see dppf_last_hip_error()              */
+  DPPF_ENOMEM = -3,  /* host or device allocation failed in dppf_plan_create              */
+  DPPF_ELIMIT = -4   /* a size exceeds what the library supports (see DPPF_MAX_WORKERS)   */
+};
+
+#define DPPF_MAX_WORKERS 1024
+
+/* Message for a return code (static storage, never NULL). */
+const char* dppf_strerror(int code);
+/* hipError_t (as int) of the most recent failed HIP call on this host thread, 0 if none. */
+int dppf_last_hip_error(void);
+
+/* ---------------------------------------------------------------------------------------
+ * Plan: everything that depends only on the shape of the problem (M, the tensor sizes) --
+ * the tile list that maps thread blocks to pieces of tensors, device copies of pointer
+ * tables, the per-block partial sums of the norm reduction, the per-worker coefficients.
+ * Creating a plan allocates device memory and synchronises; no later call does.
+ * ------------------------------------------------------------------------------------- */
+typedef struct dppf_plan dppf_plan;
+
+/* numel: HOST array of T element counts.  Uses the current HIP device.  */
+int dppf_plan_create(dppf_plan** out, int M, int T, const int64_t* numel);
+int dppf_plan_destroy(dppf_plan* plan);
+/* d = sum of numel. */
+int64_t dppf_plan_dim(const dppf_plan* plan);
+
+/* ---------------------------------------------------------------------------------------
+ * Steps of the round (Alg. 1 consensus branch with x_C = x_A; Sec. 5 Eq. 5).
+ * ------------------------------------------------------------------------------------- */
+
+/* x_A[t][i] = (1/M) sum_m x[m][t][i].   x: M*T table (read).  xbar: T table (written). */
+int dppf_replica_mean(dppf_plan* plan, const float* const* x, float* const* xbar, void* stream);
+
+/* r_out[m] = || x_m - x_A ||_2.  xbar: T table holding x_A, or NULL to recompute it from x
+ * on the fly (no extra memory traffic).  */
+int dppf_dist_norms(dppf_plan* plan, const float* const* x, const float* const* xbar,
+                    float* r_out, void* stream);
+
+/* The whole round, Eq. 5, for all workers simultaneously from the same snapshot:
+ *   c_m = pull - push / r_m  (pull if r_m == 0);  x_m <- x_m + (x_A - x_m) c_m.
+ * r_out, c_out (device, M floats) and xbar_out (T table) are optional (NULL to skip) and
+ * receive the distances, coefficients and average taken BEFORE the update.  */
+int dppf_pull_push_round(dppf_plan* plan, float* const* x, float pull, float push,
+                         float* r_out, float* c_out, float* const* xbar_out, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Local optimizer step between rounds (Alg. 1, SGD line; heavy-ball momentum, raw-gradient
+ * buffer, coupled L2 weight decay):  g' = g + wd x;  v <- mu v + g';  x <- x - lr v.
+ * x, v: M*T tables (read+written).  g: M*T table (read).
+ * ------------------------------------------------------------------------------------- */
+int dppf_local_sgd_step(dppf_plan* plan, float* const* x, float* const* v,
+                        const float* const* g, float lr, float momentum, float weight_decay,
+                        void* stream);
+
+/* Fused: exactly dppf_local_sgd_step followed by dppf_pull_push_round, but the step is
+ * folded into the round's first sweep so x is read one time less.  */
+int dppf_round(dppf_plan* plan, float* const* x, float* const* v, const float* const* g,
+               float lr, float momentum, float weight_decay, float pull, float push,
+               float* r_out, float* c_out, float* const* xbar_out, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Flat convenience forms for a plan made with T == 1: worker m's vector starts at
+ * x + m*ld (ld >= d elements).  Same semantics as the table forms above.
+ * ------------------------------------------------------------------------------------- */
+int dppf_pull_push_round_flat(dppf_plan* plan, float* x, int64_t ld, float pull, float push,
+                              float* r_out, float* c_out, float* xbar_out, void* stream);
+int dppf_local_sgd_step_flat(dppf_plan* plan, float* x, float* v, const float* g, int64_t ld,
+                             float lr, float momentum, float weight_decay, void* stream);
+int dppf_round_flat(dppf_plan* plan, float* x, float* v, const float* g, int64_t ld,
+                    float lr, float momentum, float weight_decay, float pull, float push,
+                    float* r_out, float* c_out, float* xbar_out, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Per-kernel timing with HIP events on the caller's stream (for benchmarks).  While
+ * enabled, every kernel the plan launches is bracketed by two events.  dppf_plan_timing_read
+ * waits for the recorded work, then returns up to `cap` records of the launches made since
+ * the last read: kernel_id[i] (DPPF_K_*) and ms[i].  Returns the number of records, or a
+ * negative error code.  Disabled by default; when disabled nothing is recorded.
+ * ------------------------------------------------------------------------------------- */
+enum {
+  DPPF_K_REDUCE = 0,       /* sweep 1 of the round: average + squared distances          */
+  DPPF_K_STEP_REDUCE = 1,  /* sweep 1 of the fused round: local step + average + dists   */
+  DPPF_K_FINALIZE = 2,     /* partial sums -> r_m, c_m                                   */
+  DPPF_K_UPDATE = 3,       /* sweep 2 of the round: Eq. 5                                */
+  DPPF_K_LOCAL_STEP = 4,   /* stand-alone local step                                     */
+  DPPF_K_MEAN = 5          /* stand-alone average                                        */
+};
+int dppf_plan_timing_enable(dppf_plan* plan, int enable);
+int dppf_plan_timing_read(dppf_plan* plan, int* kernel_id, float* ms, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPPF_H_ */

@@ -1,0 +1,978 @@
+// DPPF consensus round and local step for MI355X (gfx950, wave64).
+//
+// The work is bandwidth-bound streaming over the M workers' parameter tensors, so the design
+// is about bytes, not flops:
+//   * the round is two sweeps over x with a tiny finalize step between them, because the
+//     per-worker coefficient alpha - lambda/r_m (Sec. 5, Eq. 5) needs r_m, a reduction over
+//     the whole model: sweep 1 reads x once (average kept in registers, squared distances
+//     accumulated), sweep 2 reads x again, recomputes the average from the same M loads and
+//     writes x.  12 bytes per replica-parameter; the fused form folds the last local step
+//     (Alg. 1, SGD line) into sweep 1 for 28 bytes instead of 32.
+//   * a tensor list is cut into tiles of kTileElems consecutive elements of one tensor;
+//     thread blocks walk the tile list with a grid stride, so one launch covers any number
+//     of tensors of any size.  Loads are 16-byte vectors with 4-byte alignment (legal for
+//     global memory on gfx9), so no tensor needs 16-byte alignment; only the last, partial
+//     vector of a tensor is handled element by element.
+//   * squared distances: fp32 inside a tile (16 values per lane), fp64 across tiles, lanes,
+//     waves and blocks, in a fixed order -- results are bit-reproducible run to run.
+//   * sweep 2 walks the tiles in the opposite order to sweep 1, so that the part of x that
+//     sweep 1 touched last is still in the last-level cache when sweep 2 starts.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "dppf.h"
+
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef f4 f4u __attribute__((aligned(4)));   // 16-byte vector that may sit on any 4-byte boundary
+
+constexpr int kBlock = 256;                   // threads per block (4 waves)
+constexpr int kTileElems = 4096;              // elements of ONE worker's tensor per tile
+constexpr int kVecPerThread = kTileElems / (4 * kBlock);   // 16-byte vectors per thread per tile
+constexpr int kMaxTemplM = 8;                 // worker counts with a register-resident kernel
+constexpr int kMaxBlocksPerCU = 8;
+
+struct Tile {
+  long long offset;   // first element inside the tensor
+  int tensor;         // index into the tensor list
+  int count;          // 1..kTileElems elements
+};
+
+struct Coef {
+  float c;            // alpha - lambda / r_m
+  int skip;           // r_m == 0: leave the worker untouched
+};
+
+// ------------------------------------------------------------------------------- helpers
+template <bool FULL>
+__device__ __forceinline__ f4 load4(const float* p, int n) {
+  if (FULL || n >= 4) return *reinterpret_cast<const f4u*>(p);
+  f4 r = {0.f, 0.f, 0.f, 0.f};
+  if (n > 0) r.x = p[0];
+  if (n > 1) r.y = p[1];
+  if (n > 2) r.z = p[2];
+  return r;
+}
+
+template <bool FULL>
+__device__ __forceinline__ f4 load4_stream(const float* p, int n) {   // data not needed again soon
+  if (FULL || n >= 4) return __builtin_nontemporal_load(reinterpret_cast<const f4u*>(p));
+  return load4<false>(p, n);
+}
+
+template <bool FULL>
+__device__ __forceinline__ void store4(float* p, f4 v, int n) {
+  if (FULL || n >= 4) { *reinterpret_cast<f4u*>(p) = v; return; }
+  if (n > 0) p[0] = v.x;
+  if (n > 1) p[1] = v.y;
+  if (n > 2) p[2] = v.z;
+}
+
+template <bool FULL>
+__device__ __forceinline__ void store4_stream(float* p, f4 v, int n) {
+  if (FULL || n >= 4) { __builtin_nontemporal_store(v, reinterpret_cast<f4u*>(p)); return; }
+  store4<false>(p, v, n);
+}
+
+__device__ __forceinline__ f4 fma4(f4 a, float b, f4 c) {
+  f4 r;
+  r.x = __builtin_fmaf(a.x, b, c.x);
+  r.y = __builtin_fmaf(a.y, b, c.y);
+  r.z = __builtin_fmaf(a.z, b, c.z);
+  r.w = __builtin_fmaf(a.w, b, c.w);
+  return r;
+}
+
+__device__ __forceinline__ float sumsq4(f4 d, float acc) {
+  acc = __builtin_fmaf(d.x, d.x, acc);
+  acc = __builtin_fmaf(d.y, d.y, acc);
+  acc = __builtin_fmaf(d.z, d.z, acc);
+  acc = __builtin_fmaf(d.w, d.w, acc);
+  return acc;
+}
+
+// Average of M values written as x_0 + (sum_j (x_j - x_0)) / M: for identical replicas every
+// difference is exactly zero, so the average equals x_0 bit for bit for ANY M, and each
+// worker's gap is then exactly zero.  A power-of-two M multiplies by the exact reciprocal;
+// any other M divides (correctly rounded), so an average that is representable is hit exactly.
+__device__ __forceinline__ f4 mean_from_offsets(f4 s, f4 x0, int m_total, float inv_m) {
+  if ((m_total & (m_total - 1)) == 0) return fma4(s, inv_m, x0);
+  const float mf = static_cast<float>(m_total);
+  f4 q;
+  q.x = s.x / mf;
+  q.y = s.y / mf;
+  q.z = s.z / mf;
+  q.w = s.w / mf;
+  return q + x0;
+}
+
+template <int M>
+__device__ __forceinline__ f4 mean_of(const f4 (&x)[M], float inv_m) {
+  f4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int m = 1; m < M; ++m) s += x[m] - x[0];
+  return mean_from_offsets(s, x[0], M, inv_m);
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// Block-wide sums of M per-lane doubles; thread m < M writes the m-th sum to out[m].
+template <int M>
+__device__ __forceinline__ void block_sums_store(const double (&acc)[M], double* out) {
+  __shared__ double lds[kBlock / 64][M];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+  for (int m = 0; m < M; ++m) {
+    double s = wave_sum(acc[m]);
+    if (lane == 0) lds[wave][m] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x < M) {
+    double s = 0.0;
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) s += lds[w][threadIdx.x];
+    out[threadIdx.x] = s;
+  }
+}
+
+// --------------------------------------------------------------------- sweep 1 of the round
+// XBAR: 0 = average stays in registers, 1 = also written out, 2 = read from memory instead of
+// being recomputed (dppf_dist_norms with a given x_A).
+template <int M, int U, bool SGD, int XBAR, bool NORMS, bool FULL>
+__device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* __restrict__ xp,
+                                            float* const* __restrict__ vp,
+                                            const float* const* __restrict__ gp,
+                                            float* const* __restrict__ xbarp, float lr, float mu,
+                                            float wd, float inv_m, double (&acc)[M]) {
+  float* x[M];
+  float* v[M];
+  const float* g[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) {
+    x[m] = xp[m * T + tl.tensor] + tl.offset;
+    if (SGD) {
+      v[m] = vp[m * T + tl.tensor] + tl.offset;
+      g[m] = gp[m * T + tl.tensor] + tl.offset;
+    }
+  }
+  float* xb = (XBAR != 0) ? xbarp[tl.tensor] + tl.offset : nullptr;
+
+  float part[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) part[m] = 0.f;
+
+#pragma unroll 1
+  for (int it = 0; it < kVecPerThread / U; ++it) {
+    int e[U], n[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      e[k] = 4 * (threadIdx.x + (it * U + k) * kBlock);
+      n[k] = FULL ? 4 : tl.count - e[k];
+    }
+    f4 xv[U][M];
+    if (SGD) {
+      f4 vv[U][M], gv[U][M];
+#pragma unroll
+      for (int k = 0; k < U; ++k)
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+          xv[k][m] = load4<FULL>(x[m] + e[k], n[k]);
+          vv[k][m] = load4_stream<FULL>(v[m] + e[k], n[k]);
+          gv[k][m] = load4_stream<FULL>(g[m] + e[k], n[k]);
+        }
+#pragma unroll
+      for (int k = 0; k < U; ++k)
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+          // Alg. 1 local step with heavy-ball momentum: g' = g + wd x; v <- mu v + g'; x <- x - lr v
+          f4 ge = fma4(xv[k][m], wd, gv[k][m]);
+          f4 vn = fma4(vv[k][m], mu, ge);
+          f4 xn = fma4(vn, -lr, xv[k][m]);
+          store4_stream<FULL>(v[m] + e[k], vn, n[k]);
+          store4<FULL>(x[m] + e[k], xn, n[k]);       // read again by sweep 2: keep it cached
+          xv[k][m] = xn;
+        }
+    } else {
+#pragma unroll
+      for (int k = 0; k < U; ++k)
+#pragma unroll
+        for (int m = 0; m < M; ++m) xv[k][m] = load4<FULL>(x[m] + e[k], n[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      f4 xbar;
+      if (XBAR == 2) {
+        xbar = load4<FULL>(xb + e[k], n[k]);
+      } else {
+        xbar = mean_of<M>(xv[k], inv_m);
+        if (XBAR == 1) store4_stream<FULL>(xb + e[k], xbar, n[k]);
+      }
+      if (NORMS) {
+#pragma unroll
+        for (int m = 0; m < M; ++m) part[m] = sumsq4(xv[k][m] - xbar, part[m]);
+      }
+    }
+  }
+  if (NORMS) {
+#pragma unroll
+    for (int m = 0; m < M; ++m) acc[m] += static_cast<double>(part[m]);
+  }
+}
+
+template <int M, int U, bool SGD, int XBAR, bool NORMS>
+__global__ __launch_bounds__(kBlock) void k_sweep1(const Tile* __restrict__ tiles, int ntiles, int T,
+                                                   float* const* __restrict__ xp,
+                                                   float* const* __restrict__ vp,
+                                                   const float* const* __restrict__ gp,
+                                                   float* const* __restrict__ xbarp, float lr,
+                                                   float mu, float wd, double* __restrict__ partials,
+                                                   int pstride) {
+  double acc[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) acc[m] = 0.0;
+  const float inv_m = 1.0f / static_cast<float>(M);
+  for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const Tile tl = tiles[t];
+    if (tl.count == kTileElems)
+      sweep1_tile<M, U, SGD, XBAR, NORMS, true>(tl, T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
+    else
+      sweep1_tile<M, U, SGD, XBAR, NORMS, false>(tl, T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
+  }
+  if (NORMS) block_sums_store<M>(acc, partials + static_cast<size_t>(blockIdx.x) * pstride);
+}
+
+// ------------------------------------------------------- partial sums -> r_m and c_m (Eq. 5)
+// One block per worker; fixed summation order, fp64.
+__global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ partials, int nparts,
+                                                     int pstride, float pull, float push,
+                                                     Coef* __restrict__ coef, float* __restrict__ r_out,
+                                                     float* __restrict__ c_out) {
+  __shared__ double lds[kBlock];
+  const int m = blockIdx.x;
+  double s = 0.0;
+  for (int b = threadIdx.x; b < nparts; b += kBlock) s += partials[static_cast<size_t>(b) * pstride + m];
+  lds[threadIdx.x] = s;
+  __syncthreads();
+  for (int off = kBlock / 2; off > 0; off >>= 1) {
+    if (threadIdx.x < off) lds[threadIdx.x] += lds[threadIdx.x + off];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const double r = sqrt(lds[0]);
+    const bool zero = !(r > 0.0);
+    // a worker sitting exactly on the average has no push direction: coefficient alpha, no move
+    const double c = zero ? static_cast<double>(pull)
+                          : static_cast<double>(pull) - static_cast<double>(push) / r;
+    if (coef) {
+      coef[m].c = static_cast<float>(c);
+      coef[m].skip = zero ? 1 : 0;
+    }
+    if (r_out) r_out[m] = static_cast<float>(r);
+    if (c_out) c_out[m] = static_cast<float>(c);
+  }
+}
+
+// --------------------------------------------------------------------- sweep 2 of the round
+// Eq. 5: x_m <- x_m + (x_A - x_m) c_m, with x_A recomputed from the same M loads (XBAR == 0)
+// or read from memory (XBAR == 2).
+template <int M, int U, int XBAR, bool FULL>
+__device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* __restrict__ xp,
+                                            const float* const* __restrict__ xbarp,
+                                            const float (&c)[M], const bool (&skip)[M], float inv_m) {
+  float* x[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) x[m] = xp[m * T + tl.tensor] + tl.offset;
+  const float* xb = (XBAR == 2) ? xbarp[tl.tensor] + tl.offset : nullptr;
+#pragma unroll 1
+  for (int it = 0; it < kVecPerThread / U; ++it) {
+    int e[U], n[U];
+    f4 xv[U][M];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      e[k] = 4 * (threadIdx.x + (it * U + k) * kBlock);
+      n[k] = FULL ? 4 : tl.count - e[k];
+#pragma unroll
+      for (int m = 0; m < M; ++m) xv[k][m] = load4_stream<FULL>(x[m] + e[k], n[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      const f4 xbar = (XBAR == 2) ? load4_stream<FULL>(xb + e[k], n[k]) : mean_of<M>(xv[k], inv_m);
+#pragma unroll
+      for (int m = 0; m < M; ++m) {
+        const f4 moved = fma4(xbar - xv[k][m], c[m], xv[k][m]);
+        store4_stream<FULL>(x[m] + e[k], skip[m] ? xv[k][m] : moved, n[k]);
+      }
+    }
+  }
+}
+
+template <int M, int U, int XBAR>
+__global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tiles, int ntiles, int T,
+                                                   float* const* __restrict__ xp,
+                                                   const float* const* __restrict__ xbarp,
+                                                   const Coef* __restrict__ coef, float inv_m_total) {
+  if (static_cast<int>(blockIdx.x) >= ntiles) return;
+  float c[M];
+  bool skip[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) {
+    c[m] = coef[m].c;
+    skip[m] = coef[m].skip != 0;
+  }
+  // opposite walk order to sweep 1
+  const int last = (ntiles - 1 - static_cast<int>(blockIdx.x)) / static_cast<int>(gridDim.x);
+  for (int j = last; j >= 0; --j) {
+    const Tile tl = tiles[blockIdx.x + j * gridDim.x];
+    if (tl.count == kTileElems)
+      sweep2_tile<M, U, XBAR, true>(tl, T, xp, xbarp, c, skip, inv_m_total);
+    else
+      sweep2_tile<M, U, XBAR, false>(tl, T, xp, xbarp, c, skip, inv_m_total);
+  }
+}
+
+// ----------------------------------------------------------------- stand-alone local step
+template <int U, bool FULL>
+__device__ __forceinline__ void local_tile(float* x, float* v, const float* g, int count, float lr,
+                                           float mu, float wd) {
+#pragma unroll 1
+  for (int it = 0; it < kVecPerThread / U; ++it) {
+    int e[U], n[U];
+    f4 xv[U], vv[U], gv[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      e[k] = 4 * (threadIdx.x + (it * U + k) * kBlock);
+      n[k] = FULL ? 4 : count - e[k];
+      xv[k] = load4_stream<FULL>(x + e[k], n[k]);
+      vv[k] = load4_stream<FULL>(v + e[k], n[k]);
+      gv[k] = load4_stream<FULL>(g + e[k], n[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      const f4 ge = fma4(xv[k], wd, gv[k]);
+      const f4 vn = fma4(vv[k], mu, ge);
+      const f4 xn = fma4(vn, -lr, xv[k]);
+      store4_stream<FULL>(v + e[k], vn, n[k]);
+      store4_stream<FULL>(x + e[k], xn, n[k]);
+    }
+  }
+}
+
+template <int U>
+__global__ __launch_bounds__(kBlock) void k_local_step(const Tile* __restrict__ tiles, int ntiles, int M,
+                                                       int T, float* const* __restrict__ xp,
+                                                       float* const* __restrict__ vp,
+                                                       const float* const* __restrict__ gp, float lr,
+                                                       float mu, float wd) {
+  const long long total = static_cast<long long>(ntiles) * M;
+  for (long long j = blockIdx.x; j < total; j += gridDim.x) {
+    const int m = static_cast<int>(j / ntiles);
+    const Tile tl = tiles[j - static_cast<long long>(m) * ntiles];
+    const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
+    float* x = xp[slot] + tl.offset;
+    float* v = vp[slot] + tl.offset;
+    const float* g = gp[slot] + tl.offset;
+    if (tl.count == kTileElems)
+      local_tile<U, true>(x, v, g, tl.count, lr, mu, wd);
+    else
+      local_tile<U, false>(x, v, g, tl.count, lr, mu, wd);
+  }
+}
+
+// ------------------------------------------- average over a runtime number of workers (M > 8)
+template <bool FULL>
+__device__ __forceinline__ void mean_any_tile(const Tile tl, int M, int T,
+                                              float* const* __restrict__ xp, float* xb, float inv_m) {
+#pragma unroll 1
+  for (int it = 0; it < kVecPerThread; ++it) {
+    const int e = 4 * (threadIdx.x + it * kBlock);
+    const int n = FULL ? 4 : tl.count - e;
+    const f4 x0 = load4<FULL>(xp[tl.tensor] + tl.offset + e, n);
+    f4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int m = 1; m < M; ++m) s += load4<FULL>(xp[static_cast<size_t>(m) * T + tl.tensor] + tl.offset + e, n) - x0;
+    store4<FULL>(xb + e, mean_from_offsets(s, x0, M, inv_m), n);
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_mean_any(const Tile* __restrict__ tiles, int ntiles, int M, int T,
+                                                     float* const* __restrict__ xp,
+                                                     float* const* __restrict__ xbarp) {
+  const float inv_m = 1.0f / static_cast<float>(M);
+  for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    const Tile tl = tiles[t];
+    float* xb = xbarp[tl.tensor] + tl.offset;
+    if (tl.count == kTileElems) mean_any_tile<true>(tl, M, T, xp, xb, inv_m);
+    else mean_any_tile<false>(tl, M, T, xp, xb, inv_m);
+  }
+}
+
+// =========================================================================== host side
+thread_local int g_last_hip_error = 0;
+
+#define HIP_TRY(expr)                                  \
+  do {                                                 \
+    hipError_t e__ = (expr);                           \
+    if (e__ != hipSuccess) {                           \
+      g_last_hip_error = static_cast<int>(e__);        \
+      return DPPF_EHIP;                                \
+    }                                                  \
+  } while (0)
+
+// A device copy of a host pointer table, refreshed only when the host contents change.
+struct PtrTable {
+  std::vector<const void*> host;   // what the device copy currently holds
+  const void** staging = nullptr;  // pinned, source of the async upload
+  const void** dev = nullptr;
+  hipEvent_t uploaded = nullptr;   // marks the end of the last upload from `staging`
+  size_t cap = 0;
+  bool valid = false;
+};
+
+struct TimingRec {
+  int id;
+  hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct dppf_plan {
+  int M = 0, T = 0;
+  int device = 0;
+  int num_cu = 0;
+  long long d = 0;
+  std::vector<long long> numel;
+  int ntiles = 0;
+  Tile* tiles_dev = nullptr;
+  double* partials = nullptr;   // [max blocks][M]
+  int partials_rows = 0;
+  Coef* coef = nullptr;         // [M]
+  float* xbar_scratch = nullptr;            // d floats, only when M > kMaxTemplM
+  std::vector<long long> tensor_offset;     // start of tensor t inside xbar_scratch
+  enum Role { RX = 0, RV, RG, RXBAR, RXBAR_SCRATCH, NROLES };
+  PtrTable tab[NROLES];
+  // timing
+  bool timing = false;
+  std::vector<TimingRec> recs;
+  std::vector<hipEvent_t> event_pool;
+};
+
+namespace {
+
+int table_upload(dppf_plan* p, int role, const void* const* host, size_t n, hipStream_t s,
+                 const void*** dev_out) {
+  PtrTable& t = p->tab[role];
+  if (n == 0) {
+    *dev_out = t.dev;   // never dereferenced: no tiles
+    return DPPF_OK;
+  }
+  if (t.valid && t.host.size() == n && std::memcmp(t.host.data(), host, n * sizeof(void*)) == 0) {
+    *dev_out = t.dev;
+    return DPPF_OK;
+  }
+  // validate before touching anything
+  const size_t per_row = static_cast<size_t>(p->T);
+  for (size_t i = 0; i < n; ++i) {
+    const long long ne = p->numel[i % per_row];
+    if (ne > 0 && host[i] == nullptr) return DPPF_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(host[i]) & 3u) != 0) return DPPF_EINVAL;
+  }
+  HIP_TRY(hipEventSynchronize(t.uploaded));   // the previous upload has left the staging buffer
+  std::memcpy(t.staging, host, n * sizeof(void*));
+  HIP_TRY(hipMemcpyAsync(t.dev, t.staging, n * sizeof(void*), hipMemcpyHostToDevice, s));
+  HIP_TRY(hipEventRecord(t.uploaded, s));
+  t.host.assign(host, host + n);
+  t.valid = true;
+  *dev_out = t.dev;
+  return DPPF_OK;
+}
+
+int table_alloc(PtrTable& t, size_t n) {
+  t.cap = n;
+  if (n == 0) n = 1;
+  HIP_TRY(hipHostMalloc(reinterpret_cast<void**>(&t.staging), n * sizeof(void*), hipHostMallocDefault));
+  HIP_TRY(hipMalloc(reinterpret_cast<void**>(&t.dev), n * sizeof(void*)));
+  HIP_TRY(hipEventCreateWithFlags(&t.uploaded, hipEventDisableTiming));
+  return DPPF_OK;
+}
+
+void table_free(PtrTable& t) {
+  if (t.staging) (void)hipHostFree(t.staging);
+  if (t.dev) (void)hipFree(t.dev);
+  if (t.uploaded) (void)hipEventDestroy(t.uploaded);
+  t = PtrTable();
+}
+
+// ---- timing brackets
+int timing_begin(dppf_plan* p, int id, hipStream_t s) {
+  if (!p->timing) return DPPF_OK;
+  hipEvent_t ev[2];
+  for (int i = 0; i < 2; ++i) {
+    if (!p->event_pool.empty()) {
+      ev[i] = p->event_pool.back();
+      p->event_pool.pop_back();
+    } else {
+      HIP_TRY(hipEventCreate(&ev[i]));
+    }
+  }
+  p->recs.push_back(TimingRec{id, ev[0], ev[1]});
+  HIP_TRY(hipEventRecord(ev[0], s));
+  return DPPF_OK;
+}
+
+int timing_end(dppf_plan* p, hipStream_t s) {
+  if (!p->timing) return DPPF_OK;
+  HIP_TRY(hipEventRecord(p->recs.back().stop, s));
+  return DPPF_OK;
+}
+
+// ---- grid sizes: enough resident blocks to fill every CU, never more blocks than tiles
+template <typename K>
+int grid_for(const dppf_plan* p, K kernel, long long work_items, int* grid_out) {
+  int per_cu = 0;
+  HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBlock, 0));
+  if (per_cu < 1) per_cu = 1;
+  if (per_cu > kMaxBlocksPerCU) per_cu = kMaxBlocksPerCU;
+  long long g = static_cast<long long>(p->num_cu) * per_cu;
+  if (g > work_items) g = work_items;
+  if (g > p->partials_rows) g = p->partials_rows;
+  if (g < 1) g = 1;
+  *grid_out = static_cast<int>(g);
+  return DPPF_OK;
+}
+
+constexpr int unroll_plain(int M) { return M <= 4 ? 4 : (M <= 8 ? 2 : 1); }   // M*U <= 16 vectors
+constexpr int unroll_fused(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }   // 3*M*U <= 24 vectors
+
+#define DPPF_SWITCH_M(m_value, ...)                                \
+  switch (m_value) {                                               \
+    case 1: { constexpr int kM = 1; __VA_ARGS__ } break;           \
+    case 2: { constexpr int kM = 2; __VA_ARGS__ } break;           \
+    case 3: { constexpr int kM = 3; __VA_ARGS__ } break;           \
+    case 4: { constexpr int kM = 4; __VA_ARGS__ } break;           \
+    case 5: { constexpr int kM = 5; __VA_ARGS__ } break;           \
+    case 6: { constexpr int kM = 6; __VA_ARGS__ } break;           \
+    case 7: { constexpr int kM = 7; __VA_ARGS__ } break;           \
+    case 8: { constexpr int kM = 8; __VA_ARGS__ } break;           \
+    default: return DPPF_ELIMIT;                                   \
+  }
+
+// Launch sweep 1 over workers [m0, m0+mg) of the table (mg <= 8).
+template <bool SGD, int XBAR, bool NORMS>
+int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const void** gp,
+                  const void** xbarp, float lr, float mu, float wd, int m0, int* grid_used,
+                  hipStream_t s) {
+  float* const* x = (float* const*)(xp) + static_cast<size_t>(m0) * p->T;
+  float* const* v = vp ? (float* const*)(vp) + static_cast<size_t>(m0) * p->T : nullptr;
+  const float* const* g = gp ? (const float* const*)(gp) + static_cast<size_t>(m0) * p->T : nullptr;
+  float* const* xb = (float* const*)(xbarp);
+  DPPF_SWITCH_M(mg, {
+    constexpr int kU = SGD ? unroll_fused(kM) : unroll_plain(kM);
+    auto kern = k_sweep1<kM, kU, SGD, XBAR, NORMS>;
+    int grid = 0;
+    int rc = grid_for(p, kern, p->ntiles, &grid);
+    if (rc) return rc;
+    if (grid_used) {
+      if (*grid_used > 0) grid = *grid_used;   // later worker groups must use the same rows
+      *grid_used = grid;
+    }
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->ntiles, p->T, x, v, g, xb,
+                       lr, mu, wd, p->partials + m0, p->M);
+  })
+  HIP_TRY(hipGetLastError());
+  return DPPF_OK;
+}
+
+template <int XBAR>
+int launch_sweep2(dppf_plan* p, int mg, const void** xp, const void** xbarp, int m0, hipStream_t s) {
+  float* const* x = (float* const*)(xp) + static_cast<size_t>(m0) * p->T;
+  const float* const* xb = (const float* const*)(xbarp);
+  DPPF_SWITCH_M(mg, {
+    constexpr int kU = unroll_plain(kM);
+    auto kern = k_sweep2<kM, kU, XBAR>;
+    int grid = 0;
+    int rc = grid_for(p, kern, p->ntiles, &grid);
+    if (rc) return rc;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->ntiles, p->T, x, xb,
+                       p->coef + m0, 1.0f / static_cast<float>(kM));
+  })
+  HIP_TRY(hipGetLastError());
+  return DPPF_OK;
+}
+
+int launch_finalize(dppf_plan* p, int nparts, float pull, float push, bool want_coef, float* r_out,
+                    float* c_out, hipStream_t s) {
+  int rc = timing_begin(p, DPPF_K_FINALIZE, s);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_finalize, dim3(p->M), dim3(kBlock), 0, s, p->partials, nparts, p->M, pull, push,
+                     want_coef ? p->coef : nullptr, r_out, c_out);
+  HIP_TRY(hipGetLastError());
+  return timing_end(p, s);
+}
+
+int launch_local_step(dppf_plan* p, const void** xp, const void** vp, const void** gp, float lr,
+                      float mu, float wd, hipStream_t s) {
+  auto kern = k_local_step<4>;
+  int grid = 0;
+  int rc = grid_for(p, kern, static_cast<long long>(p->ntiles) * p->M, &grid);
+  if (rc) return rc;
+  rc = timing_begin(p, DPPF_K_LOCAL_STEP, s);
+  if (rc) return rc;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->ntiles, p->M, p->T,
+                     (float* const*)(xp), (float* const*)(vp),
+                     (const float* const*)(gp), lr, mu, wd);
+  HIP_TRY(hipGetLastError());
+  return timing_end(p, s);
+}
+
+int launch_mean_any(dppf_plan* p, const void** xp, const void** xbarp, hipStream_t s) {
+  int grid = 0;
+  int rc = grid_for(p, k_mean_any, p->ntiles, &grid);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_mean_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->ntiles, p->M, p->T,
+                     (float* const*)(xp), (float* const*)(xbarp));
+  HIP_TRY(hipGetLastError());
+  return DPPF_OK;
+}
+
+// The scratch average used when M > 8: a pointer table into the plan's own d-vector.
+int scratch_xbar_table(dppf_plan* p, hipStream_t s, const void*** dev_out) {
+  std::vector<const void*> host(static_cast<size_t>(p->T));
+  for (int t = 0; t < p->T; ++t) host[t] = p->xbar_scratch + p->tensor_offset[t];
+  return table_upload(p, dppf_plan::RXBAR_SCRATCH, host.data(), host.size(), s, dev_out);
+}
+
+// Shared body of dppf_pull_push_round and dppf_round (with_step).
+int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, const float* const* g,
+               float lr, float mu, float wd, float pull, float push, float* r_out, float* c_out,
+               float* const* xbar_out, hipStream_t s) {
+  if (!p || !x) return DPPF_EINVAL;
+  if (with_step && (!v || !g)) return DPPF_EINVAL;
+  const size_t n = static_cast<size_t>(p->M) * p->T;
+  const void **xd = nullptr, **vd = nullptr, **gd = nullptr, **xbd = nullptr;
+  int rc;
+  if ((rc = table_upload(p, dppf_plan::RX, reinterpret_cast<const void* const*>(x), n, s, &xd))) return rc;
+  if (with_step) {
+    if ((rc = table_upload(p, dppf_plan::RV, reinterpret_cast<const void* const*>(v), n, s, &vd))) return rc;
+    if ((rc = table_upload(p, dppf_plan::RG, reinterpret_cast<const void* const*>(g), n, s, &gd))) return rc;
+  }
+  if (xbar_out) {
+    if ((rc = table_upload(p, dppf_plan::RXBAR, reinterpret_cast<const void* const*>(xbar_out),
+                           static_cast<size_t>(p->T), s, &xbd)))
+      return rc;
+  }
+  if (p->ntiles == 0) {   // d == 0: every distance is zero, nothing moves
+    return launch_finalize(p, 0, pull, push, true, r_out, c_out, s);
+  }
+  int grid = 0;
+  if (p->M <= kMaxTemplM) {
+    if ((rc = timing_begin(p, with_step ? DPPF_K_STEP_REDUCE : DPPF_K_REDUCE, s))) return rc;
+    if (with_step) {
+      rc = xbar_out ? launch_sweep1<true, 1, true>(p, p->M, xd, vd, gd, xbd, lr, mu, wd, 0, &grid, s)
+                    : launch_sweep1<true, 0, true>(p, p->M, xd, vd, gd, nullptr, lr, mu, wd, 0, &grid, s);
+    } else {
+      rc = xbar_out ? launch_sweep1<false, 1, true>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, &grid, s)
+                    : launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, &grid, s);
+    }
+    if (rc) return rc;
+    if ((rc = timing_end(p, s))) return rc;
+    if ((rc = launch_finalize(p, grid, pull, push, true, r_out, c_out, s))) return rc;
+    if ((rc = timing_begin(p, DPPF_K_UPDATE, s))) return rc;
+    if ((rc = launch_sweep2<0>(p, p->M, xd, nullptr, 0, s))) return rc;
+    return timing_end(p, s);
+  }
+  // M > 8: materialise the average once, then run the register-resident kernels over groups
+  // of up to 8 workers that read it back.
+  if (with_step && (rc = launch_local_step(p, xd, vd, gd, lr, mu, wd, s))) return rc;
+  const void** avg = xbd;
+  if (!avg && (rc = scratch_xbar_table(p, s, &avg))) return rc;
+  if ((rc = timing_begin(p, DPPF_K_MEAN, s))) return rc;
+  if ((rc = launch_mean_any(p, xd, avg, s))) return rc;
+  if ((rc = timing_end(p, s))) return rc;
+  if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
+  for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
+    const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
+    if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, &grid, s))) return rc;
+  }
+  if ((rc = timing_end(p, s))) return rc;
+  if ((rc = launch_finalize(p, grid, pull, push, true, r_out, c_out, s))) return rc;
+  if ((rc = timing_begin(p, DPPF_K_UPDATE, s))) return rc;
+  for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
+    const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
+    if ((rc = launch_sweep2<2>(p, mg, xd, avg, m0, s))) return rc;
+  }
+  return timing_end(p, s);
+}
+
+}  // namespace
+
+// =============================================================================== C ABI
+extern "C" {
+
+const char* dppf_strerror(int code) {
+  switch (code) {
+    case DPPF_OK: return "ok";
+    case DPPF_EINVAL: return "invalid argument";
+    case DPPF_EHIP: return "HIP runtime call failed";
+    case DPPF_ENOMEM: return "out of memory";
+    case DPPF_ELIMIT: return "size exceeds a library limit";
+    default: return "unknown dppf error code";
+  }
+}
+
+int dppf_last_hip_error(void) { return g_last_hip_error; }
+
+int dppf_plan_destroy(dppf_plan* p) {
+  if (!p) return DPPF_OK;
+  for (int r = 0; r < dppf_plan::NROLES; ++r) table_free(p->tab[r]);
+  if (p->tiles_dev) (void)hipFree(p->tiles_dev);
+  if (p->partials) (void)hipFree(p->partials);
+  if (p->coef) (void)hipFree(p->coef);
+  if (p->xbar_scratch) (void)hipFree(p->xbar_scratch);
+  for (auto& r : p->recs) {
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  for (auto e : p->event_pool) (void)hipEventDestroy(e);
+  delete p;
+  return DPPF_OK;
+}
+
+int dppf_plan_create(dppf_plan** out, int M, int T, const int64_t* numel) {
+  if (!out) return DPPF_EINVAL;
+  *out = nullptr;
+  if (M < 1 || T < 0 || (T > 0 && !numel)) return DPPF_EINVAL;
+  if (M > DPPF_MAX_WORKERS) return DPPF_ELIMIT;
+  dppf_plan* p = new (std::nothrow) dppf_plan();
+  if (!p) return DPPF_ENOMEM;
+  std::vector<Tile> tiles;
+  p->M = M;
+  p->T = T;
+  try {
+    p->numel.resize(static_cast<size_t>(T));
+    p->tensor_offset.resize(static_cast<size_t>(T) + 1, 0);
+    for (int t = 0; t < T; ++t) {
+      if (numel[t] < 0) { delete p; return DPPF_EINVAL; }
+      p->numel[t] = numel[t];
+      p->tensor_offset[t] = p->d;
+      p->d += numel[t];
+      for (long long off = 0; off < numel[t]; off += kTileElems) {
+        const long long left = numel[t] - off;
+        tiles.push_back(Tile{off, t, static_cast<int>(left < kTileElems ? left : kTileElems)});
+      }
+      if (tiles.size() > static_cast<size_t>(INT32_MAX / 2)) { delete p; return DPPF_ELIMIT; }
+    }
+    p->tensor_offset[T] = p->d;
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return DPPF_ENOMEM;
+  }
+  p->ntiles = static_cast<int>(tiles.size());
+
+#define PLAN_TRY(expr)                                                             \
+  do {                                                                             \
+    hipError_t e__ = (expr);                                                       \
+    if (e__ != hipSuccess) {                                                       \
+      g_last_hip_error = static_cast<int>(e__);                                    \
+      dppf_plan_destroy(p);                                                        \
+      return e__ == hipErrorOutOfMemory ? DPPF_ENOMEM : DPPF_EHIP;                 \
+    }                                                                              \
+  } while (0)
+
+  PLAN_TRY(hipGetDevice(&p->device));
+  hipDeviceProp_t prop;
+  PLAN_TRY(hipGetDeviceProperties(&prop, p->device));
+  p->num_cu = prop.multiProcessorCount;
+  p->partials_rows = p->num_cu * kMaxBlocksPerCU;
+  PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->tiles_dev), (tiles.size() + 1) * sizeof(Tile)));
+  if (!tiles.empty())
+    PLAN_TRY(hipMemcpy(p->tiles_dev, tiles.data(), tiles.size() * sizeof(Tile), hipMemcpyHostToDevice));
+  PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->partials),
+                     static_cast<size_t>(p->partials_rows) * M * sizeof(double)));
+  PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->coef), static_cast<size_t>(M) * sizeof(Coef)));
+  if (M > kMaxTemplM && p->d > 0)
+    PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->xbar_scratch), static_cast<size_t>(p->d) * sizeof(float)));
+  const size_t n = static_cast<size_t>(M) * T;
+  for (int r = 0; r < dppf_plan::NROLES; ++r) {
+    const bool per_model = (r == dppf_plan::RXBAR || r == dppf_plan::RXBAR_SCRATCH);
+    if (table_alloc(p->tab[r], per_model ? static_cast<size_t>(T) : n) != DPPF_OK) {
+      dppf_plan_destroy(p);
+      return DPPF_EHIP;
+    }
+  }
+  PLAN_TRY(hipDeviceSynchronize());
+#undef PLAN_TRY
+  *out = p;
+  return DPPF_OK;
+}
+
+int64_t dppf_plan_dim(const dppf_plan* p) { return p ? p->d : 0; }
+
+int dppf_replica_mean(dppf_plan* p, const float* const* x, float* const* xbar, void* stream) {
+  if (!p || !x || !xbar) return DPPF_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const void **xd = nullptr, **xbd = nullptr;
+  int rc;
+  if ((rc = table_upload(p, dppf_plan::RX, reinterpret_cast<const void* const*>(x),
+                         static_cast<size_t>(p->M) * p->T, s, &xd)))
+    return rc;
+  if ((rc = table_upload(p, dppf_plan::RXBAR, reinterpret_cast<const void* const*>(xbar),
+                         static_cast<size_t>(p->T), s, &xbd)))
+    return rc;
+  if (p->ntiles == 0) return DPPF_OK;
+  if ((rc = timing_begin(p, DPPF_K_MEAN, s))) return rc;
+  if (p->M <= kMaxTemplM)
+    rc = launch_sweep1<false, 1, false>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, nullptr, s);
+  else
+    rc = launch_mean_any(p, xd, xbd, s);
+  if (rc) return rc;
+  return timing_end(p, s);
+}
+
+int dppf_dist_norms(dppf_plan* p, const float* const* x, const float* const* xbar, float* r_out,
+                    void* stream) {
+  if (!p || !x || !r_out) return DPPF_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const void **xd = nullptr, **xbd = nullptr;
+  int rc;
+  if ((rc = table_upload(p, dppf_plan::RX, reinterpret_cast<const void* const*>(x),
+                         static_cast<size_t>(p->M) * p->T, s, &xd)))
+    return rc;
+  if (xbar && (rc = table_upload(p, dppf_plan::RXBAR, reinterpret_cast<const void* const*>(xbar),
+                                 static_cast<size_t>(p->T), s, &xbd)))
+    return rc;
+  if (p->ntiles == 0) return launch_finalize(p, 0, 0.f, 0.f, false, r_out, nullptr, s);
+  int grid = 0;
+  if (p->M <= kMaxTemplM) {
+    if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
+    rc = xbar ? launch_sweep1<false, 2, true>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, &grid, s)
+              : launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, &grid, s);
+    if (rc) return rc;
+    if ((rc = timing_end(p, s))) return rc;
+  } else {
+    const void** avg = xbd;
+    if (!avg) {
+      if ((rc = scratch_xbar_table(p, s, &avg))) return rc;
+      if ((rc = launch_mean_any(p, xd, avg, s))) return rc;
+    }
+    if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
+    for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
+      const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
+      if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, &grid, s))) return rc;
+    }
+    if ((rc = timing_end(p, s))) return rc;
+  }
+  return launch_finalize(p, grid, 0.f, 0.f, false, r_out, nullptr, s);
+}
+
+int dppf_pull_push_round(dppf_plan* p, float* const* x, float pull, float push, float* r_out,
+                         float* c_out, float* const* xbar_out, void* stream) {
+  return round_impl(p, false, x, nullptr, nullptr, 0.f, 0.f, 0.f, pull, push, r_out, c_out, xbar_out,
+                    static_cast<hipStream_t>(stream));
+}
+
+int dppf_local_sgd_step(dppf_plan* p, float* const* x, float* const* v, const float* const* g, float lr,
+                        float momentum, float weight_decay, void* stream) {
+  if (!p || !x || !v || !g) return DPPF_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t n = static_cast<size_t>(p->M) * p->T;
+  const void **xd = nullptr, **vd = nullptr, **gd = nullptr;
+  int rc;
+  if ((rc = table_upload(p, dppf_plan::RX, reinterpret_cast<const void* const*>(x), n, s, &xd))) return rc;
+  if ((rc = table_upload(p, dppf_plan::RV, reinterpret_cast<const void* const*>(v), n, s, &vd))) return rc;
+  if ((rc = table_upload(p, dppf_plan::RG, reinterpret_cast<const void* const*>(g), n, s, &gd))) return rc;
+  if (p->ntiles == 0) return DPPF_OK;
+  return launch_local_step(p, xd, vd, gd, lr, momentum, weight_decay, s);
+}
+
+int dppf_round(dppf_plan* p, float* const* x, float* const* v, const float* const* g, float lr,
+               float momentum, float weight_decay, float pull, float push, float* r_out, float* c_out,
+               float* const* xbar_out, void* stream) {
+  return round_impl(p, true, x, v, g, lr, momentum, weight_decay, pull, push, r_out, c_out, xbar_out,
+                    static_cast<hipStream_t>(stream));
+}
+
+// ---- flat forms (T == 1): build the M-entry tables on the stack of the call
+static int flat_check(const dppf_plan* p, const void* base, int64_t ld) {
+  if (!p || p->T != 1 || !base || ld < p->d) return DPPF_EINVAL;
+  return DPPF_OK;
+}
+
+int dppf_pull_push_round_flat(dppf_plan* p, float* x, int64_t ld, float pull, float push, float* r_out,
+                              float* c_out, float* xbar_out, void* stream) {
+  int rc = flat_check(p, x, ld);
+  if (rc) return rc;
+  std::vector<float*> xt(static_cast<size_t>(p->M));
+  for (int m = 0; m < p->M; ++m) xt[m] = x + static_cast<long long>(m) * ld;
+  float* xb[1] = {xbar_out};
+  return dppf_pull_push_round(p, xt.data(), pull, push, r_out, c_out, xbar_out ? xb : nullptr, stream);
+}
+
+int dppf_local_sgd_step_flat(dppf_plan* p, float* x, float* v, const float* g, int64_t ld, float lr,
+                             float momentum, float weight_decay, void* stream) {
+  int rc = flat_check(p, x, ld);
+  if (rc) return rc;
+  if (!v || !g) return DPPF_EINVAL;
+  std::vector<float*> xt(p->M), vt(p->M);
+  std::vector<const float*> gt(p->M);
+  for (int m = 0; m < p->M; ++m) {
+    xt[m] = x + static_cast<long long>(m) * ld;
+    vt[m] = v + static_cast<long long>(m) * ld;
+    gt[m] = g + static_cast<long long>(m) * ld;
+  }
+  return dppf_local_sgd_step(p, xt.data(), vt.data(), gt.data(), lr, momentum, weight_decay, stream);
+}
+
+int dppf_round_flat(dppf_plan* p, float* x, float* v, const float* g, int64_t ld, float lr, float momentum,
+                    float weight_decay, float pull, float push, float* r_out, float* c_out, float* xbar_out,
+                    void* stream) {
+  int rc = flat_check(p, x, ld);
+  if (rc) return rc;
+  if (!v || !g) return DPPF_EINVAL;
+  std::vector<float*> xt(p->M), vt(p->M);
+  std::vector<const float*> gt(p->M);
+  for (int m = 0; m < p->M; ++m) {
+    xt[m] = x + static_cast<long long>(m) * ld;
+    vt[m] = v + static_cast<long long>(m) * ld;
+    gt[m] = g + static_cast<long long>(m) * ld;
+  }
+  float* xb[1] = {xbar_out};
+  return dppf_round(p, xt.data(), vt.data(), gt.data(), lr, momentum, weight_decay, pull, push, r_out,
+                    c_out, xbar_out ? xb : nullptr, stream);
+}
+
+// ---- timing
+int dppf_plan_timing_enable(dppf_plan* p, int enable) {
+  if (!p) return DPPF_EINVAL;
+  p->timing = enable != 0;
+  return DPPF_OK;
+}
+
+int dppf_plan_timing_read(dppf_plan* p, int* kernel_id, float* ms, int cap) {
+  if (!p || cap < 0 || (cap > 0 && (!kernel_id || !ms))) return DPPF_EINVAL;
+  int n = 0;
+  for (auto& r : p->recs) {
+    HIP_TRY(hipEventSynchronize(r.stop));
+    if (n < cap) {
+      float t = 0.f;
+      HIP_TRY(hipEventElapsedTime(&t, r.start, r.stop));
+      kernel_id[n] = r.id;
+      ms[n] = t;
+      ++n;
+    }
+    p->event_pool.push_back(r.start);
+    p->event_pool.push_back(r.stop);
+  }
+  p->recs.clear();
+  return n;
+}
+
+}  // extern "C"

@@ -1,0 +1,213 @@
+"""ctypes binding of the DPPF C-ABI library (include/dppf.h).
+
+Argument marshalling only: every step of the round runs in the library's HIP kernels.
+PyTorch supplies device memory (``tensor.data_ptr()``) and the stream; nothing here computes.
+There is no fallback: if the native library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "libdppf.so")
+_lib = None
+
+KERNEL_NAMES = {0: "reduce", 1: "step_reduce", 2: "finalize", 3: "update", 4: "local_step", 5: "mean",
+                6: "adamw_step", 7: "unit_mean", 8: "update_exact", 9: "pull_then_push"}
+
+
+class DppfError(RuntimeError):
+    pass
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load libdppf.so (built in-tree by ``python -m paper_2507_20424_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise DppfError(f"{_LIB_PATH} is missing: build it with `python -m paper_2507_20424_amd.build`; "
+                        "there is no CPU fallback")
+    lib = ctypes.CDLL(_LIB_PATH)
+    c_fpp = ctypes.POINTER(ctypes.c_void_p)
+    vp, f, i64 = ctypes.c_void_p, ctypes.c_float, ctypes.c_int64
+    sigs = {
+        "dppf_strerror": (ctypes.c_char_p, [ctypes.c_int]),
+        "dppf_last_hip_error": (ctypes.c_int, []),
+        "dppf_plan_create": (ctypes.c_int, [ctypes.POINTER(vp), ctypes.c_int, ctypes.c_int, ctypes.POINTER(i64)]),
+        "dppf_plan_destroy": (ctypes.c_int, [vp]),
+        "dppf_plan_dim": (i64, [vp]),
+        "dppf_replica_mean": (ctypes.c_int, [vp, c_fpp, c_fpp, vp]),
+        "dppf_dist_norms": (ctypes.c_int, [vp, c_fpp, c_fpp, vp, vp]),
+        "dppf_pull_push_round": (ctypes.c_int, [vp, c_fpp, f, f, vp, vp, c_fpp, vp]),
+        "dppf_local_sgd_step": (ctypes.c_int, [vp, c_fpp, c_fpp, c_fpp, f, f, f, vp]),
+        "dppf_round": (ctypes.c_int, [vp, c_fpp, c_fpp, c_fpp, f, f, f, f, f, vp, vp, c_fpp, vp]),
+        "dppf_pull_push_round_flat": (ctypes.c_int, [vp, vp, i64, f, f, vp, vp, vp, vp]),
+        "dppf_local_sgd_step_flat": (ctypes.c_int, [vp, vp, vp, vp, i64, f, f, f, vp]),
+        "dppf_round_flat": (ctypes.c_int, [vp, vp, vp, vp, i64, f, f, f, f, f, vp, vp, vp, vp]),
+        "dppf_plan_timing_enable": (ctypes.c_int, [vp, ctypes.c_int]),
+        "dppf_plan_timing_read": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(f), ctypes.c_int]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc < 0:
+        lib = load()
+        msg = lib.dppf_strerror(rc).decode()
+        raise DppfError(f"{what}: {msg} (code {rc}, hip error {lib.dppf_last_hip_error()})")
+
+
+class PointerTable:
+    """A host array of device pointers, built once and reused across calls.
+
+    ``tensors`` is either a list of M lists of T tensors (per-worker table, worker-major) or a
+    flat list of T tensors (per-model table).  The tensors are kept alive by the table."""
+
+    def __init__(self, tensors: Sequence):
+        if len(tensors) > 0 and isinstance(tensors[0], (list, tuple)):
+            flat = [t for row in tensors for t in row]
+        else:
+            flat = list(tensors)
+        self.keep = flat
+        self.n = len(flat)
+        self.array = (ctypes.c_void_p * max(self.n, 1))()
+        for i, t in enumerate(flat):
+            self.array[i] = t.data_ptr() if hasattr(t, "data_ptr") else int(t)
+
+    @property
+    def ptr(self):
+        return ctypes.cast(self.array, ctypes.POINTER(ctypes.c_void_p))
+
+
+def _table(obj) -> Optional[PointerTable]:
+    if obj is None or isinstance(obj, PointerTable):
+        return obj
+    return PointerTable(obj)
+
+
+def _tptr(tab: Optional[PointerTable]):
+    return tab.ptr if tab is not None else None
+
+
+def _dev(t) -> Optional[int]:
+    if t is None:
+        return None
+    return t.data_ptr() if hasattr(t, "data_ptr") else int(t)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if hasattr(stream, "cuda_stream"):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+class Plan:
+    """Shape-dependent state of the library for M workers and a list of tensor sizes."""
+
+    def __init__(self, M: int, numel: Sequence[int]):
+        lib = load()
+        self.M, self.T = int(M), len(numel)
+        self.numel = [int(n) for n in numel]
+        arr = (ctypes.c_int64 * max(self.T, 1))(*self.numel)
+        handle = ctypes.c_void_p()
+        _check(lib.dppf_plan_create(ctypes.byref(handle), self.M, self.T, arr), "dppf_plan_create")
+        self._h = handle
+        self._lib = lib
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            self._lib.dppf_plan_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def d(self) -> int:
+        return int(self._lib.dppf_plan_dim(self._h))
+
+    def _expect(self, tab: PointerTable, n: int, name: str) -> None:
+        if tab.n != n:
+            raise DppfError(f"{name}: table has {tab.n} pointers, the plan needs {n}")
+
+    # ---- steps of the round
+    def replica_mean(self, x, xbar, stream=None) -> None:
+        x, xbar = _table(x), _table(xbar)
+        self._expect(x, self.M * self.T, "x"); self._expect(xbar, self.T, "xbar")
+        _check(self._lib.dppf_replica_mean(self._h, x.ptr, xbar.ptr, _stream(stream)), "dppf_replica_mean")
+
+    def dist_norms(self, x, r_out, xbar=None, stream=None) -> None:
+        x, xbar = _table(x), _table(xbar)
+        self._expect(x, self.M * self.T, "x")
+        if xbar is not None:
+            self._expect(xbar, self.T, "xbar")
+        _check(self._lib.dppf_dist_norms(self._h, x.ptr, _tptr(xbar), _dev(r_out), _stream(stream)),
+               "dppf_dist_norms")
+
+    def pull_push_round(self, x, pull, push, r_out=None, c_out=None, xbar_out=None, stream=None) -> None:
+        x, xbar_out = _table(x), _table(xbar_out)
+        self._expect(x, self.M * self.T, "x")
+        if xbar_out is not None:
+            self._expect(xbar_out, self.T, "xbar_out")
+        _check(self._lib.dppf_pull_push_round(self._h, x.ptr, pull, push, _dev(r_out), _dev(c_out),
+                                              _tptr(xbar_out), _stream(stream)), "dppf_pull_push_round")
+
+    def local_sgd_step(self, x, v, g, lr, momentum, weight_decay=0.0, stream=None) -> None:
+        x, v, g = _table(x), _table(v), _table(g)
+        for tab, name in ((x, "x"), (v, "v"), (g, "g")):
+            self._expect(tab, self.M * self.T, name)
+        _check(self._lib.dppf_local_sgd_step(self._h, x.ptr, v.ptr, g.ptr, lr, momentum, weight_decay,
+                                             _stream(stream)), "dppf_local_sgd_step")
+
+    def round(self, x, v, g, lr, momentum, weight_decay, pull, push, r_out=None, c_out=None,
+              xbar_out=None, stream=None) -> None:
+        x, v, g, xbar_out = _table(x), _table(v), _table(g), _table(xbar_out)
+        for tab, name in ((x, "x"), (v, "v"), (g, "g")):
+            self._expect(tab, self.M * self.T, name)
+        if xbar_out is not None:
+            self._expect(xbar_out, self.T, "xbar_out")
+        _check(self._lib.dppf_round(self._h, x.ptr, v.ptr, g.ptr, lr, momentum, weight_decay, pull, push,
+                                    _dev(r_out), _dev(c_out), _tptr(xbar_out), _stream(stream)), "dppf_round")
+
+    # ---- flat forms (T == 1); x, v, g are [M, ld] tensors or raw device addresses
+    def pull_push_round_flat(self, x, ld, pull, push, r_out=None, c_out=None, xbar_out=None, stream=None):
+        _check(self._lib.dppf_pull_push_round_flat(self._h, _dev(x), ld, pull, push, _dev(r_out), _dev(c_out),
+                                                   _dev(xbar_out), _stream(stream)), "dppf_pull_push_round_flat")
+
+    def local_sgd_step_flat(self, x, v, g, ld, lr, momentum, weight_decay=0.0, stream=None):
+        _check(self._lib.dppf_local_sgd_step_flat(self._h, _dev(x), _dev(v), _dev(g), ld, lr, momentum,
+                                                  weight_decay, _stream(stream)), "dppf_local_sgd_step_flat")
+
+    def round_flat(self, x, v, g, ld, lr, momentum, weight_decay, pull, push, r_out=None, c_out=None,
+                   xbar_out=None, stream=None):
+        _check(self._lib.dppf_round_flat(self._h, _dev(x), _dev(v), _dev(g), ld, lr, momentum, weight_decay,
+                                         pull, push, _dev(r_out), _dev(c_out), _dev(xbar_out),
+                                         _stream(stream)), "dppf_round_flat")
+
+    # ---- per-kernel timing
+    def timing_enable(self, enable: bool = True) -> None:
+        _check(self._lib.dppf_plan_timing_enable(self._h, 1 if enable else 0), "dppf_plan_timing_enable")
+
+    def timing_read(self, cap: int = 4096) -> List[tuple]:
+        ids = (ctypes.c_int * cap)()
+        ms = (ctypes.c_float * cap)()
+        n = self._lib.dppf_plan_timing_read(self._h, ids, ms, cap)
+        _check(n, "dppf_plan_timing_read")
+        return [(KERNEL_NAMES.get(ids[i], str(ids[i])), float(ms[i])) for i in range(n)]

@@ -4,18 +4,21 @@ This module holds no arithmetic of the method.  It only (a) lists tensor shapes 
 model families the paper trains (ResNet-50/101, ViT-B/16, PyramidNet; Sec. 6 and the
 experiment details in the appendix) so that the per-layer size mix is realistic, and
 (b) draws the random numbers (initial point, per-worker spread, per-step gradients) with
-numpy's PCG64 generator in one fixed order.  Both the CPU oracle's tests and the GPU
-path's tests/benchmarks consume the arrays produced here; neither side's code is used.
+numpy's PCG64 generator.  Both the CPU oracle's tests and the GPU path's tests/benchmarks
+consume the arrays produced here; neither side's code is used.
 
-Draw order (all float32 standard normals scaled by the stated sigma):
-  1. (heterogeneous workloads only) the M log-uniform worker spreads sigma_m,
-  2. x0, tensor by tensor in list order,
-  3. for m = 0..M-1: the worker's offset noise, tensor by tensor,
-  4. for every call of ``next_grads()``: for m = 0..M-1, the gradient, tensor by tensor.
-Momentum buffers start at zero.
+Every random array is a flat float32 vector of length d (the tensor list concatenated in
+list order) with its own stream, addressed by a spawn key under SeedSequence(seed):
+  (0,)        the M log-uniform worker spreads sigma_m (heterogeneous workloads only)
+  (1,)        x0 ~ N(0, sigma_x0^2)
+  (2, m)      worker m's offset: x_m = x0 + N(0, sigma_m^2)
+  (3, k, m)   worker m's gradient at local step k ~ N(0, sigma_grad^2)
+A vector is cut into 8 equal segments, each filled from the stream (key..., segment), so the
+values do not depend on how many threads do the filling.  Momentum buffers start at zero.
 """
 from __future__ import annotations
 
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 from typing import List, Sequence, Tuple
 
@@ -138,6 +141,29 @@ def small_spec(name: str = "small_ragged", M: int = 4, seed: int = 7, tau: int =
     return WorkloadSpec(name, M, tuple(tuple(s) for s in shapes), seed=seed, tau=tau, **kw)
 
 
+_SEGMENTS = 8
+
+
+def _normal_vector(seed: int, key: Tuple[int, ...], n: int) -> np.ndarray:
+    """n standard normals (float32) from the streams (key..., 0..7)."""
+    out = np.empty(n, dtype=np.float32)
+    bounds = [(n * s) // _SEGMENTS for s in range(_SEGMENTS + 1)]
+
+    def fill(seg: int) -> None:
+        a, b = bounds[seg], bounds[seg + 1]
+        if b > a:
+            ss = np.random.SeedSequence(entropy=seed, spawn_key=tuple(key) + (seg,))
+            np.random.Generator(np.random.PCG64(ss)).standard_normal(out=out[a:b], dtype=np.float32)
+
+    if n >= (1 << 20):
+        with ThreadPoolExecutor(_SEGMENTS) as pool:
+            list(pool.map(fill, range(_SEGMENTS)))
+    else:
+        for seg in range(_SEGMENTS):
+            fill(seg)
+    return out
+
+
 @dataclass
 class HostInputs:
     """Host arrays for one workload.  x[m] and v[m] are flat float32 vectors of length d
@@ -147,15 +173,13 @@ class HostInputs:
     v: List[np.ndarray]
     offsets: np.ndarray
     sigma_m: np.ndarray
-    _rng: np.random.Generator = field(repr=False, default=None)
 
-    def next_grads(self) -> List[np.ndarray]:
-        """Draw the next step's gradients: for each worker, tensor by tensor."""
+    def grads(self, step: int) -> List[np.ndarray]:
+        """The gradients of local step `step` (0-based), one flat vector per worker."""
         spec = self.spec
         out = []
-        for _m in range(spec.M):
-            g = np.empty(spec.d, dtype=np.float32)
-            _fill_normal(self._rng, g, self.offsets)
+        for m in range(spec.M):
+            g = _normal_vector(spec.seed, (3, step, m), spec.d)
             g *= np.float32(spec.sigma_grad)
             out.append(g)
         return out
@@ -165,31 +189,23 @@ class HostInputs:
         return [flat[o[t]:o[t + 1]] for t in range(len(o) - 1)]
 
 
-def _fill_normal(rng: np.random.Generator, flat: np.ndarray, offsets: np.ndarray) -> None:
-    for t in range(len(offsets) - 1):
-        a, b = int(offsets[t]), int(offsets[t + 1])
-        if b > a:
-            rng.standard_normal(out=flat[a:b], dtype=np.float32)
-
-
 def make_inputs(spec: WorkloadSpec) -> HostInputs:
-    rng = np.random.Generator(np.random.PCG64(spec.seed))
     offsets = np.zeros(spec.T + 1, dtype=np.int64)
     np.cumsum(np.asarray(spec.numel, dtype=np.int64), out=offsets[1:])
     d = spec.d
     if spec.hetero_spread:
-        sigma_m = (10.0 ** rng.uniform(-4.0, -2.0, size=spec.M)).astype(np.float32)
+        ss = np.random.SeedSequence(entropy=spec.seed, spawn_key=(0,))
+        u = np.random.Generator(np.random.PCG64(ss)).uniform(-4.0, -2.0, size=spec.M)
+        sigma_m = (10.0 ** u).astype(np.float32)
     else:
         sigma_m = np.full(spec.M, spec.sigma_worker, dtype=np.float32)
-    x0 = np.empty(d, dtype=np.float32)
-    _fill_normal(rng, x0, offsets)
+    x0 = _normal_vector(spec.seed, (1,), d)
     x0 *= np.float32(spec.sigma_x0)
     xs, vs = [], []
     for m in range(spec.M):
-        noise = np.empty(d, dtype=np.float32)
-        _fill_normal(rng, noise, offsets)
+        noise = _normal_vector(spec.seed, (2, m), d)
         noise *= sigma_m[m]
         noise += x0
         xs.append(noise)
         vs.append(np.zeros(d, dtype=np.float32))
-    return HostInputs(spec, xs, vs, offsets, sigma_m, rng)
+    return HostInputs(spec, xs, vs, offsets, sigma_m)

@@ -1,0 +1,130 @@
+"""Shared helpers of the GPU parity tests: device buffers for a workload, the oracle driven
+over the same host arrays, and the comparison rules.
+
+Tolerances (fp32 kernels against the float64 oracle):
+  parameters   |gpu - oracle| <= 1e-5 |oracle| + (4 + 2 tau) 2^-24 max|tensor|
+               The relative term is the stated bar.  The absolute term covers elements that
+               end up near zero by cancellation: each local step rounds x and v once
+               (<= 1 ulp of the operands per step, tau steps), the round adds the rounding of
+               the average, of the gap and of the final fused multiply-add (<= 4 ulp of the
+               operands).  It is about 1e-6 of the tensor's largest element.
+  r_m, c_m     relative 1e-4
+  update       || (gpu x+ - x_pre) - (oracle x+ - x_pre) ||_2 <= 1e-3 || oracle x+ - x_pre ||_2
+               so that a wrong or missing push cannot hide inside the parameter tolerance.
+"""
+from __future__ import annotations
+
+import os
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from oracle import dppf_oracle as O  # noqa: E402
+
+EPS32 = 2.0 ** -24
+
+
+def f32(v: float) -> float:
+    """A hyper-parameter as the C ABI will see it (rounded to float32), as a Python float."""
+    return float(np.float32(v))
+
+
+# ------------------------------------------------------------------ device side
+def upload_tensors(flat: np.ndarray, offsets: np.ndarray, misalign: int = 0):
+    """One separately allocated device tensor per list entry (like a model's parameters).
+    With misalign = k in 1..3 every tensor starts k elements past an aligned address."""
+    import torch
+    out = []
+    for t in range(len(offsets) - 1):
+        a, b = int(offsets[t]), int(offsets[t + 1])
+        buf = torch.empty(b - a + misalign, dtype=torch.float32, device="cuda")
+        view = buf[misalign:]
+        if b > a:
+            view.copy_(torch.from_numpy(flat[a:b]))
+        out.append(view)
+    return out
+
+
+def download(tensors) -> np.ndarray:
+    import torch
+    if len(tensors) == 0:
+        return np.zeros(0, dtype=np.float32)
+    return torch.cat([t.reshape(-1) for t in tensors]).cpu().numpy()
+
+
+def download_rows(rows) -> np.ndarray:
+    return np.stack([download(r) for r in rows])
+
+
+# ------------------------------------------------------------------ oracle side
+def oracle_local_steps(x, v, grads_of_step, tau, lr, mu, wd, block=1 << 20, threads=8):
+    """tau oracle local steps.  The step is defined element by element, so the oracle function
+    is applied to column blocks (in threads) -- the values are those of one unblocked call."""
+    x = np.array(x, dtype=np.float64)
+    v = np.array(v, dtype=np.float64)
+    d = x.shape[1]
+    for k in range(tau):
+        g = np.stack(grads_of_step(k))
+        if d <= block:
+            x, v = O.local_sgd_step(x, v, g, lr, mu, wd)
+            continue
+
+        def one(a):
+            xs, vs = O.local_sgd_step(x[:, a:a + block], v[:, a:a + block], g[:, a:a + block], lr, mu, wd)
+            x[:, a:a + block] = xs
+            v[:, a:a + block] = vs
+
+        with ThreadPoolExecutor(threads) as pool:
+            list(pool.map(one, range(0, d, block)))
+    return x, v
+
+
+# ------------------------------------------------------------------ comparisons
+def per_element_scale(ref: np.ndarray, offsets: np.ndarray) -> np.ndarray:
+    """max |ref| of the tensor each element belongs to (over all workers)."""
+    T = len(offsets) - 1
+    scale_t = np.zeros(T, dtype=np.float64)
+    for t in range(T):
+        a, b = int(offsets[t]), int(offsets[t + 1])
+        if b > a:
+            scale_t[t] = np.max(np.abs(ref[:, a:b]))
+    return np.repeat(scale_t, np.diff(offsets))
+
+
+def assert_params_close(gpu: np.ndarray, ref: np.ndarray, offsets: np.ndarray, tau: int, what: str):
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    if ref.size == 0:
+        return
+    assert np.all(np.isfinite(gpu)), f"{what}: non-finite values"
+    scale = per_element_scale(ref, offsets)
+    for m in range(ref.shape[0]):
+        err = np.abs(gpu[m].astype(np.float64) - ref[m])
+        tol = 1e-5 * np.abs(ref[m]) + (4 + 2 * tau) * EPS32 * scale
+        bad = err > tol
+        if bad.any():
+            i = int(np.argmax(err - tol))
+            raise AssertionError(f"{what}: worker {m}, {int(bad.sum())} elements out of tolerance; worst at {i}: "
+                                 f"gpu {gpu[m, i]!r} oracle {ref[m, i]!r} err {err[i]:.3e} tol {tol[i]:.3e}")
+
+
+def assert_rel(gpu, ref, rtol: float, what: str):
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
+    err = np.abs(gpu - ref)
+    assert np.all(err <= rtol * np.abs(ref)), f"{what}: gpu {gpu} oracle {ref} rel {err / np.maximum(np.abs(ref), 1e-300)}"
+
+
+def assert_update_close(gpu_new: np.ndarray, ref_new: np.ndarray, x_pre: np.ndarray, what: str):
+    for m in range(ref_new.shape[0]):
+        upd = ref_new[m] - x_pre[m]
+        nrm = np.linalg.norm(upd)
+        if nrm == 0.0:
+            continue
+        diff = np.linalg.norm((gpu_new[m].astype(np.float64) - x_pre[m]) - upd)
+        assert diff <= 1e-3 * nrm, f"{what}: worker {m} update error {diff / nrm:.3e}"

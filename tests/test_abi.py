@@ -1,0 +1,77 @@
+"""Host-side checks that need no GPU: the library loads, exports every symbol the header
+declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2507_20424_amd import dppf
+    if not os.path.exists(dppf.lib_path()):
+        from paper_2507_20424_amd.build import build_library
+        build_library(verbose=False)
+    return dppf.load()
+
+
+def header_symbols():
+    with open(os.path.join(ROOT, "include", "dppf.h")) as f:
+        text = f.read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dppf_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = header_symbols()
+    assert len(names) >= 14 and "dppf_round" in names and "dppf_plan_create" in names
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in include/dppf.h but not exported"
+
+
+def test_binding_covers_the_header(lib):
+    from paper_2507_20424_amd import dppf
+    for name in header_symbols():
+        assert getattr(lib, name).argtypes is not None, f"binding has no signature for {name}"
+    for method in ("replica_mean", "dist_norms", "pull_push_round", "local_sgd_step", "round"):
+        assert hasattr(dppf.Plan, method)
+
+
+def test_error_strings(lib):
+    assert lib.dppf_strerror(0) == b"ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert lib.dppf_strerror(code)
+    assert lib.dppf_last_hip_error() == 0
+
+
+def test_plan_create_rejects_bad_arguments(lib):
+    h = ctypes.c_void_p()
+    one = (ctypes.c_int64 * 1)(8)
+    neg = (ctypes.c_int64 * 1)(-1)
+    assert lib.dppf_plan_create(None, 2, 1, one) == -1
+    assert lib.dppf_plan_create(ctypes.byref(h), 0, 1, one) == -1
+    assert lib.dppf_plan_create(ctypes.byref(h), 2, -1, one) == -1
+    assert lib.dppf_plan_create(ctypes.byref(h), 2, 1, None) == -1
+    assert lib.dppf_plan_create(ctypes.byref(h), 2, 1, neg) == -1
+    assert lib.dppf_plan_create(ctypes.byref(h), 1025, 1, one) == -4
+    assert not h.value
+    assert lib.dppf_plan_destroy(None) == 0
+
+
+def test_null_plan_is_rejected(lib):
+    assert lib.dppf_pull_push_round(None, None, 0.1, 0.01, None, None, None, None) == -1
+    assert lib.dppf_round(None, None, None, None, 0.1, 0.9, 0.0, 0.1, 0.01, None, None, None, None) == -1
+    assert lib.dppf_local_sgd_step(None, None, None, None, 0.1, 0.9, 0.0, None) == -1
+    assert lib.dppf_replica_mean(None, None, None, None) == -1
+    assert lib.dppf_dist_norms(None, None, None, None, None) == -1
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    from paper_2507_20424_amd import dppf
+    monkeypatch.setattr(dppf, "_lib", None)
+    monkeypatch.setattr(dppf, "_LIB_PATH", str(tmp_path / "libdppf.so"))
+    with pytest.raises(dppf.DppfError):
+        dppf.load()

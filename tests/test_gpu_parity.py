@@ -1,0 +1,336 @@
+"""GPU parity: every entry point of the C ABI against the CPU oracle on the same seeded
+inputs, element by element, on lists that span several tiles and have ragged tails, plus the
+degenerate cases of the method."""
+import numpy as np
+import pytest
+
+from parity import (O, assert_params_close, assert_rel, assert_update_close, download, download_rows, f32,
+                    upload_tensors)
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+from paper_2507_20424_amd import dppf, workloads as W  # noqa: E402
+
+
+def _dev_rows(inp, arrays, misalign=0):
+    return [upload_tensors(a, inp.offsets, misalign) for a in arrays]
+
+
+def _hyper(spec):
+    return dict(lr=f32(spec.lr), mu=f32(spec.momentum), wd=f32(spec.weight_decay), pull=f32(spec.pull),
+                push=f32(spec.push))
+
+
+WORKER_COUNTS = [1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 16]
+
+
+@pytest.mark.parametrize("M", WORKER_COUNTS)
+@pytest.mark.parametrize("misalign", [0, 1])
+def test_round_small_lists(M, misalign):
+    spec = W.small_spec(M=M, seed=100 + M)
+    h = _hyper(spec)
+    inp = W.make_inputs(spec)
+    x_host = np.stack(inp.x)
+    x = _dev_rows(inp, inp.x, misalign)
+    xbar = upload_tensors(np.zeros(spec.d, np.float32), inp.offsets, misalign)
+    r = torch.zeros(M, device="cuda")
+    c = torch.zeros(M, device="cuda")
+    plan = dppf.Plan(M, spec.numel)
+
+    ref_new, ref_r, ref_c, ref_avg = O.pull_push_round(x_host, h["pull"], h["push"])
+
+    # the pieces on their own
+    plan.replica_mean(x, xbar)
+    assert_params_close(download(xbar)[None], ref_avg[None], inp.offsets, 0, "replica_mean")
+    plan.dist_norms(x, r)
+    if M > 1:
+        assert_rel(r.cpu().numpy(), ref_r, 1e-4, "dist_norms")
+    r.zero_()
+    plan.dist_norms(x, r, xbar=xbar)
+    if M > 1:
+        assert_rel(r.cpu().numpy(), O.dist_norms(x_host, download(xbar)), 1e-4, "dist_norms(given average)")
+    assert np.array_equal(download_rows(x), x_host), "read-only entry points changed x"
+
+    # the round
+    xbar2 = upload_tensors(np.zeros(spec.d, np.float32), inp.offsets, misalign)
+    plan.pull_push_round(x, h["pull"], h["push"], r_out=r, c_out=c, xbar_out=xbar2)
+    got = download_rows(x)
+    if M > 1:
+        assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+        assert_rel(c.cpu().numpy(), ref_c, 1e-4, "c")
+    assert_params_close(got, ref_new, inp.offsets, 0, "pull_push_round x")
+    assert_update_close(got, ref_new, x_host.astype(np.float64), "pull_push_round")
+    assert_params_close(download(xbar2)[None], ref_avg[None], inp.offsets, 0, "xbar_out")
+    plan.close()
+
+
+@pytest.mark.parametrize("M", [2, 4, 8, 9])
+@pytest.mark.parametrize("wd", [0.0, 1e-3])
+def test_local_step_and_fused_round(M, wd):
+    spec = W.small_spec(M=M, seed=200 + M, tau=3, weight_decay=wd)
+    h = _hyper(spec)
+    inp = W.make_inputs(spec)
+    plan = dppf.Plan(M, spec.numel)
+    x = _dev_rows(inp, inp.x, 2)
+    v = _dev_rows(inp, inp.v, 3)
+    xo, vo = np.stack(inp.x).astype(np.float64), np.stack(inp.v).astype(np.float64)
+    # tau - 1 stand-alone steps, then the fused last step + round
+    for k in range(spec.tau - 1):
+        gk = inp.grads(k)
+        g = _dev_rows(inp, gk, 1)
+        plan.local_sgd_step(x, v, g, h["lr"], h["mu"], h["wd"])
+        xo, vo = O.local_sgd_step(xo, vo, np.stack(gk), h["lr"], h["mu"], h["wd"])
+        assert_params_close(download_rows(x), xo, inp.offsets, k + 1, f"local step {k} x")
+        assert_params_close(download_rows(v), vo, inp.offsets, k + 1, f"local step {k} v")
+    gk = inp.grads(spec.tau - 1)
+    g = _dev_rows(inp, gk, 0)
+    g_before = download_rows(g)
+    r = torch.zeros(M, device="cuda")
+    c = torch.zeros(M, device="cuda")
+    xbar = upload_tensors(np.zeros(spec.d, np.float32), inp.offsets)
+    x_pre, _ = O.local_sgd_step(xo, vo, np.stack(gk), h["lr"], h["mu"], h["wd"])
+    ref_x, ref_v, ref_r, ref_c, ref_avg = O.dppf_round(xo, vo, np.stack(gk), h["lr"], h["mu"], h["wd"],
+                                                       h["pull"], h["push"])
+    plan.round(x, v, g, h["lr"], h["mu"], h["wd"], h["pull"], h["push"], r_out=r, c_out=c, xbar_out=xbar)
+    got_x, got_v = download_rows(x), download_rows(v)
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "fused r")
+    assert_rel(c.cpu().numpy(), ref_c, 1e-4, "fused c")
+    assert_params_close(got_x, ref_x, inp.offsets, spec.tau, "fused x")
+    assert_params_close(got_v, ref_v, inp.offsets, spec.tau, "fused v")
+    assert_params_close(download(xbar)[None], ref_avg[None], inp.offsets, spec.tau, "fused xbar")
+    assert_update_close(got_x, ref_x, x_pre, "fused round")
+    assert np.array_equal(download_rows(g), g_before), "gradients were modified"
+    plan.close()
+
+
+def test_fused_equals_step_then_round_bitwise():
+    # dppf_round is defined as dppf_local_sgd_step followed by dppf_pull_push_round
+    spec = W.small_spec(M=4, seed=31)
+    h = _hyper(spec)
+    inp = W.make_inputs(spec)
+    gk = inp.grads(0)
+    plan = dppf.Plan(4, spec.numel)
+    res = []
+    for fused in (True, False):
+        x, v, g = _dev_rows(inp, inp.x), _dev_rows(inp, inp.v), _dev_rows(inp, gk)
+        r = torch.zeros(4, device="cuda")
+        if fused:
+            plan.round(x, v, g, h["lr"], h["mu"], h["wd"], h["pull"], h["push"], r_out=r)
+        else:
+            plan.local_sgd_step(x, v, g, h["lr"], h["mu"], h["wd"])
+            plan.pull_push_round(x, h["pull"], h["push"], r_out=r)
+        res.append((download_rows(x), download_rows(v), r.cpu().numpy()))
+    assert np.array_equal(res[0][0], res[1][0]) and np.array_equal(res[0][1], res[1][1])
+    assert np.array_equal(res[0][2], res[1][2])
+    plan.close()
+
+
+@pytest.mark.parametrize("M", [2, 3, 4, 7, 8, 12])
+def test_identical_replicas_do_not_move(M):
+    # zero distance: no direction, no displacement, r = 0, c = alpha, no NaN/Inf -- bit for bit,
+    # negative zeros included
+    spec = W.small_spec(M=M, seed=5)
+    inp = W.make_inputs(spec)
+    row = inp.x[0].copy()
+    row[::7] = -0.0
+    rows = [row.copy() for _ in range(M)]
+    x = _dev_rows(inp, rows, 1)
+    r = torch.full((M,), -1.0, device="cuda")
+    c = torch.full((M,), -1.0, device="cuda")
+    plan = dppf.Plan(M, spec.numel)
+    plan.pull_push_round(x, f32(0.3), f32(0.7), r_out=r, c_out=c)
+    got = download_rows(x)
+    assert np.array_equal(got.view(np.uint32), np.stack(rows).view(np.uint32))
+    assert np.all(r.cpu().numpy() == 0.0)
+    assert np.all(c.cpu().numpy() == np.float32(0.3))
+    plan.close()
+
+
+def test_one_worker_on_the_average():
+    # worker 2 sits exactly on the average of the other two: it must stay, the others move
+    base = ((np.arange(5000) - 2500) / 1024.0).astype(np.float32)      # exact in binary
+    delta = np.full(5000, 0.25, np.float32)
+    rows = [base - delta, base + delta, base.copy()]
+    x_host = np.stack(rows)
+    offsets = np.array([0, 5000])
+    x = [upload_tensors(a, offsets) for a in rows]
+    r = torch.zeros(3, device="cuda")
+    plan = dppf.Plan(3, [5000])
+    plan.pull_push_round(x, f32(0.5), f32(0.25), r_out=r)
+    ref_new, ref_r, _, _ = O.pull_push_round(x_host, f32(0.5), f32(0.25))
+    got = download_rows(x)
+    assert ref_r[2] == 0.0 and r.cpu().numpy()[2] == 0.0
+    assert np.array_equal(got[2], rows[2])
+    assert_params_close(got, ref_new, offsets, 0, "x")
+    plan.close()
+
+
+def test_special_cases_of_the_update():
+    spec = W.small_spec(M=4, seed=9)
+    inp = W.make_inputs(spec)
+    x_host = np.stack(inp.x).astype(np.float64)
+    avg = x_host.mean(axis=0)
+    plan = dppf.Plan(4, spec.numel)
+    # alpha = 1, lambda = 0: everybody lands on the average (LocalSGD / gradient averaging)
+    x = _dev_rows(inp, inp.x)
+    plan.pull_push_round(x, 1.0, 0.0)
+    got = download_rows(x)
+    for m in range(4):
+        assert np.max(np.abs(got[m] - avg)) <= 2 * 2.0 ** -24 * np.max(np.abs(avg))
+    # lambda = 0: the average is preserved, gaps shrink by (1 - alpha)
+    x = _dev_rows(inp, inp.x)
+    r0 = torch.zeros(4, device="cuda")
+    r1 = torch.zeros(4, device="cuda")
+    plan.pull_push_round(x, f32(0.25), 0.0, r_out=r0)
+    got = download_rows(x).astype(np.float64)
+    assert np.max(np.abs(got.mean(axis=0) - avg)) <= 4 * 2.0 ** -24 * np.max(np.abs(avg))
+    plan.dist_norms(x, r1)
+    assert_rel(r1.cpu().numpy(), 0.75 * r0.cpu().numpy().astype(np.float64), 1e-4, "gap shrink")
+    # alpha = 0: every worker moves exactly lambda, away from the average
+    x = _dev_rows(inp, inp.x)
+    lam = f32(0.05)
+    plan.pull_push_round(x, 0.0, lam)
+    got = download_rows(x).astype(np.float64)
+    step = got - x_host
+    assert_rel(np.linalg.norm(step, axis=1), np.full(4, lam), 1e-4, "push-only step length")
+    assert np.all(np.sum(step * (x_host - avg), axis=1) > 0)
+    plan.close()
+
+
+def test_empty_and_tiny_lists():
+    # no tensors at all; tensors of size zero inside a list; d smaller than one vector
+    r = torch.full((3,), -1.0, device="cuda")
+    c = torch.full((3,), -1.0, device="cuda")
+    plan = dppf.Plan(3, [])
+    plan.pull_push_round([[], [], []], f32(0.1), f32(0.2), r_out=r, c_out=c)
+    assert np.all(r.cpu().numpy() == 0) and np.all(c.cpu().numpy() == np.float32(0.1))
+    plan.close()
+
+    spec = W.small_spec(M=2, seed=3, shapes=((0,), (1,), (0,), (2,), (0,)))
+    inp = W.make_inputs(spec)
+    x = _dev_rows(inp, inp.x)
+    plan = dppf.Plan(2, spec.numel)
+    r = torch.zeros(2, device="cuda")
+    plan.pull_push_round(x, f32(0.1), f32(0.01), r_out=r)
+    ref_new, ref_r, _, _ = O.pull_push_round(np.stack(inp.x), f32(0.1), f32(0.01))
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+    assert_params_close(download_rows(x), ref_new, inp.offsets, 0, "x")
+    plan.close()
+
+
+def test_flat_forms_with_padding():
+    M, d, ld = 4, 10_001, 10_240
+    spec = W.small_spec(M=M, seed=17, shapes=((d,),))
+    h = _hyper(spec)
+    inp = W.make_inputs(spec)
+    gk = inp.grads(0)
+
+    def padded(rows, fill):
+        buf = torch.full((M, ld), fill, dtype=torch.float32, device="cuda")
+        buf[:, :d] = torch.from_numpy(np.stack(rows)).cuda()
+        return buf
+
+    x, v, g = padded(inp.x, 7.0), padded(inp.v, 8.0), padded(gk, 9.0)
+    r = torch.zeros(M, device="cuda")
+    c = torch.zeros(M, device="cuda")
+    xbar = torch.zeros(d, device="cuda")
+    plan = dppf.Plan(M, [d])
+    xo, vo = O.local_sgd_step(np.stack(inp.x), np.stack(inp.v), np.stack(gk), h["lr"], h["mu"], h["wd"])
+    plan.local_sgd_step_flat(x, v, g, ld, h["lr"], h["mu"], h["wd"])
+    assert_params_close(x[:, :d].cpu().numpy(), xo, inp.offsets, 1, "flat step x")
+    ref_x, ref_v, ref_r, ref_c, ref_avg = O.dppf_round(xo, vo, np.stack(gk), h["lr"], h["mu"], h["wd"],
+                                                       h["pull"], h["push"])
+    plan.round_flat(x, v, g, ld, h["lr"], h["mu"], h["wd"], h["pull"], h["push"], r_out=r, c_out=c, xbar_out=xbar)
+    assert_params_close(x[:, :d].cpu().numpy(), ref_x, inp.offsets, 2, "flat fused x")
+    assert_params_close(v[:, :d].cpu().numpy(), ref_v, inp.offsets, 2, "flat fused v")
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "flat r")
+    assert_params_close(xbar.cpu().numpy()[None], ref_avg[None], inp.offsets, 2, "flat xbar")
+    x2, r2, c2, _ = O.pull_push_round(ref_x, h["pull"], h["push"])
+    plan.pull_push_round_flat(x, ld, h["pull"], h["push"], r_out=r, c_out=c)
+    assert_rel(r.cpu().numpy(), r2, 1e-4, "flat round r")
+    assert_params_close(x[:, :d].cpu().numpy(), x2, inp.offsets, 3, "flat round x")
+    # the padding between workers is never touched
+    assert torch.all(x[:, d:] == 7.0) and torch.all(v[:, d:] == 8.0) and torch.all(g[:, d:] == 9.0)
+    plan.close()
+
+
+def test_argument_errors_on_device():
+    plan = dppf.Plan(2, [8, 8])
+    a = torch.zeros(16, device="cuda")
+    good = [[a[:8], a[8:]], [a[:8], a[8:]]]
+    with pytest.raises(dppf.DppfError):
+        plan.pull_push_round([[a[:8]], [a[:8]]], 0.1, 0.1)            # wrong table length
+    lib = dppf.load()
+    import ctypes
+    tab = dppf.PointerTable(good)
+    tab.array[1] = tab.array[1] + 2                                    # not 4-byte aligned
+    assert lib.dppf_pull_push_round(plan._h, tab.ptr, 0.1, 0.1, None, None, None, None) == -1
+    tab.array[1] = None                                                # null tensor of nonzero size
+    assert lib.dppf_pull_push_round(plan._h, tab.ptr, 0.1, 0.1, None, None, None, None) == -1
+    assert lib.dppf_dist_norms(plan._h, dppf.PointerTable(good).ptr, None, None, None) == -1
+    flat_plan = dppf.Plan(2, [8])
+    assert lib.dppf_pull_push_round_flat(flat_plan._h, ctypes.c_void_p(a.data_ptr()), 4, 0.1, 0.1, None, None,
+                                         None, None) == -1             # ld < d
+    assert lib.dppf_pull_push_round_flat(plan._h, ctypes.c_void_p(a.data_ptr()), 8, 0.1, 0.1, None, None,
+                                         None, None) == -1             # plan has T != 1
+    torch.cuda.synchronize()
+    assert torch.all(a == 0)
+    plan.close()
+    flat_plan.close()
+
+
+def test_results_are_reproducible_bitwise():
+    spec = W.small_spec(M=4, seed=77, shapes=((300_000,), (17,), (123_457,)))
+    inp = W.make_inputs(spec)
+    plan = dppf.Plan(4, spec.numel)
+    outs = []
+    for _ in range(3):
+        x = _dev_rows(inp, inp.x)
+        r = torch.zeros(4, device="cuda")
+        plan.pull_push_round(x, f32(0.1), f32(0.01), r_out=r)
+        outs.append((download_rows(x), r.cpu().numpy()))
+    for o in outs[1:]:
+        assert np.array_equal(o[0], outs[0][0]) and np.array_equal(o[1], outs[0][1])
+    plan.close()
+
+
+def test_pointer_tables_can_change_between_calls():
+    spec = W.small_spec(M=2, seed=41)
+    inp = W.make_inputs(spec)
+    plan = dppf.Plan(2, spec.numel)
+    ref_new, ref_r, _, _ = O.pull_push_round(np.stack(inp.x), f32(0.1), f32(0.01))
+    r = torch.zeros(2, device="cuda")
+    for _ in range(3):                       # fresh allocations every time -> new tables
+        x = _dev_rows(inp, inp.x)
+        plan.pull_push_round(x, f32(0.1), f32(0.01), r_out=r)
+        assert_params_close(download_rows(x), ref_new, inp.offsets, 0, "x")
+        assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+    plan.close()
+
+
+def test_non_default_stream_and_timing_records():
+    spec = W.small_spec(M=4, seed=43)
+    h = _hyper(spec)
+    inp = W.make_inputs(spec)
+    gk = inp.grads(0)
+    plan = dppf.Plan(4, spec.numel)
+    s = torch.cuda.Stream()
+    x, v, g = _dev_rows(inp, inp.x), _dev_rows(inp, inp.v), _dev_rows(inp, gk)
+    r = torch.zeros(4, device="cuda")
+    torch.cuda.synchronize()
+    plan.timing_enable(True)
+    with torch.cuda.stream(s):
+        plan.round(x, v, g, h["lr"], h["mu"], h["wd"], h["pull"], h["push"], r_out=r)
+    recs = plan.timing_read()
+    plan.timing_enable(False)
+    assert [name for name, _ in recs] == ["step_reduce", "finalize", "update"]
+    assert all(ms > 0 for _, ms in recs)
+    s.synchronize()
+    ref_x, _, ref_r, _, _ = O.dppf_round(np.stack(inp.x), np.stack(inp.v), np.stack(gk), h["lr"], h["mu"],
+                                         h["wd"], h["pull"], h["push"])
+    assert_params_close(download_rows(x), ref_x, inp.offsets, 1, "x on a side stream")
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+    assert plan.timing_read() == []
+    plan.close()

@@ -26,9 +26,10 @@ def test_generator_reproducible_and_scaled():
         assert np.array_equal(a.x[m], b.x[m])
         assert a.x[m].dtype == np.float32 and a.x[m].shape == (spec.d,)
         assert not a.v[m].any()
-    ga, gb = a.next_grads(), b.next_grads()
+    ga, gb = a.grads(0), b.grads(0)
     assert all(np.array_equal(p, q) for p, q in zip(ga, gb))
-    assert not np.array_equal(ga[0], a.next_grads()[0])
+    assert not np.array_equal(ga[0], a.grads(1)[0])
+    assert not np.array_equal(ga[0], ga[1])
     assert a.offsets[-1] == spec.d and len(a.tensor_views(a.x[0])) == spec.T
 
 
@@ -38,7 +39,7 @@ def test_value_scales():
     x = np.stack(inp.x).astype(np.float64)
     assert abs(x.std() / 0.02 - 1) < 0.01
     assert abs((x[0] - x[1]).std() / (np.sqrt(2) * 1e-3) - 1) < 0.01
-    g = inp.next_grads()
+    g = inp.grads(0)
     assert abs(g[0].std() / 1e-2 - 1) < 0.01
     het = W.make_inputs(W.small_spec(M=8, seed=4, hetero_spread=True))
     assert np.all(het.sigma_m >= 1e-4) and np.all(het.sigma_m <= 1e-2)
