@@ -25,7 +25,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
 # algorithmic HBM bytes per replica-parameter (fp32): what the method itself must move
 BYTES_PER_RP = {
-    "step_reduce": 20.0,        # read x, v, g; write x, v (average and distances ride along)
+    "step_reduce": 16.0,        # read x, v, g; write v (average and distances ride along)
+    "step_update": 12.0,        # read x, v; write x
     "reduce": 4.0,              # read x
     "update": 8.0,              # read x, write x
     "local_step": 20.0,         # read x, v, g; write x, v
@@ -77,7 +78,7 @@ def main() -> int:
     ap.add_argument("--workload", default="vitb16_M4")
     ap.add_argument("--call", default="round", choices=sorted(CALL_BYTES))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-cols", type=int, default=40_000_000)
+    ap.add_argument("--cpu-sample-cols", type=int, default=1_000_000_000)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU (the M workers are M replicas resident in one GPU's "

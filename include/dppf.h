@@ -127,14 +127,24 @@ int dppf_round_flat(dppf_plan* plan, float* x, float* v, const float* g, int64_t
  * ------------------------------------------------------------------------------------- */
 enum {
   DPPF_K_REDUCE = 0,       /* sweep 1 of the round: average + squared distances          */
-  DPPF_K_STEP_REDUCE = 1,  /* sweep 1 of the fused round: local step + average + dists   */
+  DPPF_K_STEP_REDUCE = 1,  /* sweep 1 of the fused round: local step (v stored, x not)
+                              + average + distances                                      */
   DPPF_K_FINALIZE = 2,     /* partial sums -> r_m, c_m                                   */
   DPPF_K_UPDATE = 3,       /* sweep 2 of the round: Eq. 5                                */
   DPPF_K_LOCAL_STEP = 4,   /* stand-alone local step                                     */
-  DPPF_K_MEAN = 5          /* stand-alone average                                        */
+  DPPF_K_MEAN = 5,         /* stand-alone average                                        */
+  DPPF_K_STEP_UPDATE = 6   /* sweep 2 of the fused round: x - lr v rebuilt, then Eq. 5   */
 };
 int dppf_plan_timing_enable(dppf_plan* plan, int enable);
 int dppf_plan_timing_read(dppf_plan* plan, int* kernel_id, float* ms, int cap);
+
+/* ---------------------------------------------------------------------------------------
+ * Measurement aid, not part of the method: a plain copy dst[i] = src[i] of n floats (device
+ * pointers, 4-byte aligned, non-overlapping) using the same 16-byte load/store path as the
+ * kernels above.  It gives the practical bandwidth ceiling of the device and a launch of
+ * known size (4n bytes read, 4n written) against which hardware counters can be scaled.
+ * ------------------------------------------------------------------------------------- */
+int dppf_util_copy(float* dst, const float* src, int64_t n, void* stream);
 
 #ifdef __cplusplus
 }

@@ -36,7 +36,13 @@ constexpr int kBlock = 256;                   // threads per block (4 waves)
 constexpr int kTileElems = 4096;              // elements of ONE worker's tensor per tile
 constexpr int kVecPerThread = kTileElems / (4 * kBlock);   // 16-byte vectors per thread per tile
 constexpr int kMaxTemplM = 8;                 // worker counts with a register-resident kernel
-constexpr int kMaxBlocksPerCU = 8;
+constexpr int kMaxBlocksPerCU = 8;             // upper bound on resident blocks per CU (sizes buffers)
+// Resident blocks per CU by traffic pattern.  Kernels that only read want many loads in flight;
+// kernels that mix reads and writes run fastest with ONE block per CU: fewer concurrently open
+// DRAM rows and longer same-direction bursts outweigh the lost latency hiding.
+constexpr int kBlocksPerCUReadOnly = 8;
+constexpr int kBlocksPerCUReadWrite = 1;
+constexpr bool kDeferStepStore = true;        // fused round: x after the local step is never stored
 
 struct Tile {
   long long offset;   // first element inside the tensor
@@ -199,7 +205,10 @@ __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* 
           f4 vn = fma4(vv[k][m], mu, ge);
           f4 xn = fma4(vn, -lr, xv[k][m]);
           store4_stream<FULL>(v[m] + e[k], vn, n[k]);
-          store4<FULL>(x[m] + e[k], xn, n[k]);       // read again by sweep 2: keep it cached
+          // With the deferred form the stepped x is not written here: sweep 2 re-derives it from
+          // the old x and the new v with the same fused multiply-add (same bits), which trades 4
+          // written bytes for 4 read bytes per element -- reads are the cheaper direction.
+          if (!kDeferStepStore) store4<FULL>(x[m] + e[k], xn, n[k]);
           xv[k][m] = xn;
         }
     } else {
@@ -282,16 +291,71 @@ __global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ 
   }
 }
 
+// The same reduction done by every block of sweep 2 on its own (saves a launch): all blocks
+// add the per-block partial sums of sweep 1 in the same fixed order, so all get the same bits.
+template <int M>
+__device__ __forceinline__ void coefficients_from_partials(const double* __restrict__ partials, int nparts,
+                                                           int pstride, float pull, float push,
+                                                           float (&c)[M], bool (&skip)[M],
+                                                           float* __restrict__ r_out,
+                                                           float* __restrict__ c_out) {
+  __shared__ double lds[kBlock / 64][M];
+  __shared__ float c_sh[M];
+  __shared__ int skip_sh[M];
+  double acc[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) acc[m] = 0.0;
+  for (int b = threadIdx.x; b < nparts; b += kBlock) {
+#pragma unroll
+    for (int m = 0; m < M; ++m) acc[m] += partials[static_cast<size_t>(b) * pstride + m];
+  }
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+  for (int m = 0; m < M; ++m) {
+    const double s = wave_sum(acc[m]);
+    if (lane == 0) lds[wave][m] = s;
+  }
+  __syncthreads();
+  if (threadIdx.x < M) {
+    double s = 0.0;
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) s += lds[w][threadIdx.x];
+    const double r = sqrt(s);
+    const bool zero = !(r > 0.0);
+    const double cc = zero ? static_cast<double>(pull)
+                           : static_cast<double>(pull) - static_cast<double>(push) / r;
+    c_sh[threadIdx.x] = static_cast<float>(cc);
+    skip_sh[threadIdx.x] = zero ? 1 : 0;
+    if (blockIdx.x == 0) {
+      if (r_out) r_out[threadIdx.x] = static_cast<float>(r);
+      if (c_out) c_out[threadIdx.x] = static_cast<float>(cc);
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int m = 0; m < M; ++m) {
+    c[m] = c_sh[m];
+    skip[m] = skip_sh[m] != 0;
+  }
+}
+
 // --------------------------------------------------------------------- sweep 2 of the round
 // Eq. 5: x_m <- x_m + (x_A - x_m) c_m, with x_A recomputed from the same M loads (XBAR == 0)
 // or read from memory (XBAR == 2).
-template <int M, int U, int XBAR, bool FULL>
+// STEP: x in memory is still the value from before the fused local step and v is already the
+// new momentum; the stepped x is rebuilt as x - lr v before the update.
+template <int M, int U, int XBAR, bool STEP, bool FULL>
 __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* __restrict__ xp,
-                                            const float* const* __restrict__ xbarp,
+                                            const float* const* __restrict__ vp,
+                                            const float* const* __restrict__ xbarp, float lr,
                                             const float (&c)[M], const bool (&skip)[M], float inv_m) {
   float* x[M];
+  const float* v[M];
 #pragma unroll
-  for (int m = 0; m < M; ++m) x[m] = xp[m * T + tl.tensor] + tl.offset;
+  for (int m = 0; m < M; ++m) {
+    x[m] = xp[m * T + tl.tensor] + tl.offset;
+    if (STEP) v[m] = vp[m * T + tl.tensor] + tl.offset;
+  }
   const float* xb = (XBAR == 2) ? xbarp[tl.tensor] + tl.offset : nullptr;
 #pragma unroll 1
   for (int it = 0; it < kVecPerThread / U; ++it) {
@@ -303,6 +367,17 @@ __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* 
       n[k] = FULL ? 4 : tl.count - e[k];
 #pragma unroll
       for (int m = 0; m < M; ++m) xv[k][m] = load4_stream<FULL>(x[m] + e[k], n[k]);
+    }
+    if (STEP) {
+      f4 vv[U][M];
+#pragma unroll
+      for (int k = 0; k < U; ++k)
+#pragma unroll
+        for (int m = 0; m < M; ++m) vv[k][m] = load4_stream<FULL>(v[m] + e[k], n[k]);
+#pragma unroll
+      for (int k = 0; k < U; ++k)
+#pragma unroll
+        for (int m = 0; m < M; ++m) xv[k][m] = fma4(vv[k][m], -lr, xv[k][m]);
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) {
@@ -316,27 +391,37 @@ __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* 
   }
 }
 
-template <int M, int U, int XBAR>
+// FOLD: the coefficients are derived here from sweep 1's partial sums (no finalize launch);
+// otherwise they are read from `coef`.
+template <int M, int U, int XBAR, bool STEP, bool FOLD>
 __global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tiles, int ntiles, int T,
                                                    float* const* __restrict__ xp,
-                                                   const float* const* __restrict__ xbarp,
-                                                   const Coef* __restrict__ coef, float inv_m_total) {
+                                                   const float* const* __restrict__ vp,
+                                                   const float* const* __restrict__ xbarp, float lr,
+                                                   const Coef* __restrict__ coef, float inv_m_total,
+                                                   const double* __restrict__ partials, int nparts,
+                                                   int pstride, float pull, float push,
+                                                   float* __restrict__ r_out, float* __restrict__ c_out) {
   if (static_cast<int>(blockIdx.x) >= ntiles) return;
   float c[M];
   bool skip[M];
+  if (FOLD) {
+    coefficients_from_partials<M>(partials, nparts, pstride, pull, push, c, skip, r_out, c_out);
+  } else {
 #pragma unroll
-  for (int m = 0; m < M; ++m) {
-    c[m] = coef[m].c;
-    skip[m] = coef[m].skip != 0;
+    for (int m = 0; m < M; ++m) {
+      c[m] = coef[m].c;
+      skip[m] = coef[m].skip != 0;
+    }
   }
   // opposite walk order to sweep 1
   const int last = (ntiles - 1 - static_cast<int>(blockIdx.x)) / static_cast<int>(gridDim.x);
   for (int j = last; j >= 0; --j) {
     const Tile tl = tiles[blockIdx.x + j * gridDim.x];
     if (tl.count == kTileElems)
-      sweep2_tile<M, U, XBAR, true>(tl, T, xp, xbarp, c, skip, inv_m_total);
+      sweep2_tile<M, U, XBAR, STEP, true>(tl, T, xp, vp, xbarp, lr, c, skip, inv_m_total);
     else
-      sweep2_tile<M, U, XBAR, false>(tl, T, xp, xbarp, c, skip, inv_m_total);
+      sweep2_tile<M, U, XBAR, STEP, false>(tl, T, xp, vp, xbarp, lr, c, skip, inv_m_total);
   }
 }
 
@@ -413,6 +498,16 @@ __global__ __launch_bounds__(kBlock) void k_mean_any(const Tile* __restrict__ ti
     if (tl.count == kTileElems) mean_any_tile<true>(tl, M, T, xp, xb, inv_m);
     else mean_any_tile<false>(tl, M, T, xp, xb, inv_m);
   }
+}
+
+// ---------------------------------------------- plain copy (bandwidth / counter calibration)
+__global__ __launch_bounds__(kBlock) void k_copy(float* __restrict__ dst, const float* __restrict__ src,
+                                                 long long n) {
+  const long long nvec = n / 4;
+  const long long stride = static_cast<long long>(gridDim.x) * kBlock;
+  for (long long i = static_cast<long long>(blockIdx.x) * kBlock + threadIdx.x; i < nvec; i += stride)
+    store4_stream<true>(dst + 4 * i, load4_stream<true>(src + 4 * i, 4), 4);
+  if (blockIdx.x == 0 && threadIdx.x < n - 4 * nvec) dst[4 * nvec + threadIdx.x] = src[4 * nvec + threadIdx.x];
 }
 
 // =========================================================================== host side
@@ -536,10 +631,11 @@ int timing_end(dppf_plan* p, hipStream_t s) {
 
 // ---- grid sizes: enough resident blocks to fill every CU, never more blocks than tiles
 template <typename K>
-int grid_for(const dppf_plan* p, K kernel, long long work_items, int* grid_out) {
+int grid_for(const dppf_plan* p, K kernel, long long work_items, int want_per_cu, int* grid_out) {
   int per_cu = 0;
   HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBlock, 0));
   if (per_cu < 1) per_cu = 1;
+  if (per_cu > want_per_cu) per_cu = want_per_cu;
   if (per_cu > kMaxBlocksPerCU) per_cu = kMaxBlocksPerCU;
   long long g = static_cast<long long>(p->num_cu) * per_cu;
   if (g > work_items) g = work_items;
@@ -550,6 +646,7 @@ int grid_for(const dppf_plan* p, K kernel, long long work_items, int* grid_out) 
 }
 
 constexpr int unroll_plain(int M) { return M <= 4 ? 4 : (M <= 8 ? 2 : 1); }   // M*U <= 16 vectors
+constexpr int unroll_step_update(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }   // 2*M*U <= 16 vectors
 constexpr int unroll_fused(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }   // 3*M*U <= 24 vectors
 
 #define DPPF_SWITCH_M(m_value, ...)                                \
@@ -578,7 +675,7 @@ int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const 
     constexpr int kU = SGD ? unroll_fused(kM) : unroll_plain(kM);
     auto kern = k_sweep1<kM, kU, SGD, XBAR, NORMS>;
     int grid = 0;
-    int rc = grid_for(p, kern, p->ntiles, &grid);
+    int rc = grid_for(p, kern, p->ntiles, (SGD || XBAR == 1) ? kBlocksPerCUReadWrite : kBlocksPerCUReadOnly, &grid);
     if (rc) return rc;
     if (grid_used) {
       if (*grid_used > 0) grid = *grid_used;   // later worker groups must use the same rows
@@ -591,18 +688,21 @@ int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const 
   return DPPF_OK;
 }
 
-template <int XBAR>
-int launch_sweep2(dppf_plan* p, int mg, const void** xp, const void** xbarp, int m0, hipStream_t s) {
+template <int XBAR, bool STEP, bool FOLD>
+int launch_sweep2(dppf_plan* p, int mg, const void** xp, const void** vp, const void** xbarp, float lr,
+                  int m0, int nparts, float pull, float push, float* r_out, float* c_out, hipStream_t s) {
   float* const* x = (float* const*)(xp) + static_cast<size_t>(m0) * p->T;
+  const float* const* v = vp ? (const float* const*)(vp) + static_cast<size_t>(m0) * p->T : nullptr;
   const float* const* xb = (const float* const*)(xbarp);
   DPPF_SWITCH_M(mg, {
-    constexpr int kU = unroll_plain(kM);
-    auto kern = k_sweep2<kM, kU, XBAR>;
+    constexpr int kU = STEP ? unroll_step_update(kM) : unroll_plain(kM);
+    auto kern = k_sweep2<kM, kU, XBAR, STEP, FOLD>;
     int grid = 0;
-    int rc = grid_for(p, kern, p->ntiles, &grid);
+    int rc = grid_for(p, kern, p->ntiles, kBlocksPerCUReadWrite, &grid);
     if (rc) return rc;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->ntiles, p->T, x, xb,
-                       p->coef + m0, 1.0f / static_cast<float>(kM));
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->ntiles, p->T, x, v, xb, lr,
+                       p->coef + m0, 1.0f / static_cast<float>(kM), p->partials, nparts, p->M, pull, push,
+                       r_out, c_out);
   })
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
@@ -622,7 +722,7 @@ int launch_local_step(dppf_plan* p, const void** xp, const void** vp, const void
                       float mu, float wd, hipStream_t s) {
   auto kern = k_local_step<4>;
   int grid = 0;
-  int rc = grid_for(p, kern, static_cast<long long>(p->ntiles) * p->M, &grid);
+  int rc = grid_for(p, kern, static_cast<long long>(p->ntiles) * p->M, kBlocksPerCUReadWrite, &grid);
   if (rc) return rc;
   rc = timing_begin(p, DPPF_K_LOCAL_STEP, s);
   if (rc) return rc;
@@ -635,7 +735,7 @@ int launch_local_step(dppf_plan* p, const void** xp, const void** vp, const void
 
 int launch_mean_any(dppf_plan* p, const void** xp, const void** xbarp, hipStream_t s) {
   int grid = 0;
-  int rc = grid_for(p, k_mean_any, p->ntiles, &grid);
+  int rc = grid_for(p, k_mean_any, p->ntiles, kBlocksPerCUReadWrite, &grid);
   if (rc) return rc;
   hipLaunchKernelGGL(k_mean_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->ntiles, p->M, p->T,
                      (float* const*)(xp), (float* const*)(xbarp));
@@ -684,9 +784,12 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
     }
     if (rc) return rc;
     if ((rc = timing_end(p, s))) return rc;
-    if ((rc = launch_finalize(p, grid, pull, push, true, r_out, c_out, s))) return rc;
-    if ((rc = timing_begin(p, DPPF_K_UPDATE, s))) return rc;
-    if ((rc = launch_sweep2<0>(p, p->M, xd, nullptr, 0, s))) return rc;
+    if ((rc = timing_begin(p, (with_step && kDeferStepStore) ? DPPF_K_STEP_UPDATE : DPPF_K_UPDATE, s))) return rc;
+    if (with_step && kDeferStepStore)
+      rc = launch_sweep2<0, true, true>(p, p->M, xd, vd, nullptr, lr, 0, grid, pull, push, r_out, c_out, s);
+    else
+      rc = launch_sweep2<0, false, true>(p, p->M, xd, nullptr, nullptr, 0.f, 0, grid, pull, push, r_out, c_out, s);
+    if (rc) return rc;
     return timing_end(p, s);
   }
   // M > 8: materialise the average once, then run the register-resident kernels over groups
@@ -707,7 +810,8 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
   if ((rc = timing_begin(p, DPPF_K_UPDATE, s))) return rc;
   for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
     const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
-    if ((rc = launch_sweep2<2>(p, mg, xd, avg, m0, s))) return rc;
+    if ((rc = launch_sweep2<2, false, false>(p, mg, xd, nullptr, avg, 0.f, m0, 0, 0.f, 0.f, nullptr, nullptr, s)))
+      return rc;
   }
   return timing_end(p, s);
 }
@@ -947,6 +1051,25 @@ int dppf_round_flat(dppf_plan* p, float* x, float* v, const float* g, int64_t ld
   float* xb[1] = {xbar_out};
   return dppf_round(p, xt.data(), vt.data(), gt.data(), lr, momentum, weight_decay, pull, push, r_out,
                     c_out, xbar_out ? xb : nullptr, stream);
+}
+
+// ---- plain device-to-device copy of n floats with the library's own load/store path
+int dppf_util_copy(float* dst, const float* src, int64_t n, void* stream) {
+  if (n < 0 || (n > 0 && (!dst || !src))) return DPPF_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(dst) & 3u) || (reinterpret_cast<uintptr_t>(src) & 3u)) return DPPF_EINVAL;
+  if (n == 0) return DPPF_OK;
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  int cus = 0;
+  HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  long long blocks = (n / 4 + kBlock - 1) / kBlock;
+  const long long cap = static_cast<long long>(cus) * kBlocksPerCUReadWrite;
+  if (blocks > cap) blocks = cap;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(k_copy, dim3(static_cast<unsigned>(blocks)), dim3(kBlock), 0,
+                     static_cast<hipStream_t>(stream), dst, src, static_cast<long long>(n));
+  HIP_TRY(hipGetLastError());
+  return DPPF_OK;
 }
 
 // ---- timing

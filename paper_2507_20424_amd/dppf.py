@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "li
 _lib = None
 
 KERNEL_NAMES = {0: "reduce", 1: "step_reduce", 2: "finalize", 3: "update", 4: "local_step", 5: "mean",
-                6: "adamw_step", 7: "unit_mean", 8: "update_exact", 9: "pull_then_push"}
+                6: "step_update"}
 
 
 class DppfError(RuntimeError):
@@ -50,6 +50,7 @@ def load():
         "dppf_pull_push_round_flat": (ctypes.c_int, [vp, vp, i64, f, f, vp, vp, vp, vp]),
         "dppf_local_sgd_step_flat": (ctypes.c_int, [vp, vp, vp, vp, i64, f, f, f, vp]),
         "dppf_round_flat": (ctypes.c_int, [vp, vp, vp, vp, i64, f, f, f, f, f, vp, vp, vp, vp]),
+        "dppf_util_copy": (ctypes.c_int, [vp, vp, i64, vp]),
         "dppf_plan_timing_enable": (ctypes.c_int, [vp, ctypes.c_int]),
         "dppf_plan_timing_read": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(f), ctypes.c_int]),
     }
@@ -211,3 +212,8 @@ class Plan:
         n = self._lib.dppf_plan_timing_read(self._h, ids, ms, cap)
         _check(n, "dppf_plan_timing_read")
         return [(KERNEL_NAMES.get(ids[i], str(ids[i])), float(ms[i])) for i in range(n)]
+
+
+def util_copy(dst, src, n: int, stream=None) -> None:
+    """Plain device copy of n floats through the library's load/store path (measurement aid)."""
+    _check(load().dppf_util_copy(_dev(dst), _dev(src), n, _stream(stream)), "dppf_util_copy")
