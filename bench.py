@@ -78,6 +78,8 @@ def main() -> int:
     ap.add_argument("--workload", default="vitb16_M4")
     ap.add_argument("--call", default="round", choices=sorted(CALL_BYTES))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch a plain 1 GiB copy (known size) so hardware counters can be scaled")
     ap.add_argument("--cpu-sample-cols", type=int, default=1_000_000_000)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -120,6 +122,15 @@ def main() -> int:
             plan.pull_push_round(xt, hyper["pull"], hyper["push"], r_out=r, c_out=c)
         else:
             plan.local_sgd_step(xt, vt, gt, hyper["lr"], hyper["mu"], hyper["wd"])
+
+    if args.copy_calibration:
+        n_cal = 1 << 28                     # 1 GiB read + 1 GiB written per launch
+        src = torch.ones(n_cal, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dppf.util_copy(dst, src, n_cal)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
