@@ -151,6 +151,31 @@ __device__ __forceinline__ void block_sums_store(const double (&acc)[M], double*
   }
 }
 
+// The tile list holds all full tiles first, then the partial ones (tensor tails and tensors
+// smaller than a tile).  Blocks [0, gfull) walk the full tiles with a stride of gfull; the
+// remaining blocks walk the partial tiles.  A list of many small tensors therefore does not put
+// short, latency-bound tiles into the streaming blocks' loops.
+struct TileWalk {
+  int first, end, stride;
+  bool full;
+};
+
+__device__ __forceinline__ TileWalk tile_walk(int nfull, int ntiles, int gfull) {
+  TileWalk w;
+  if (static_cast<int>(blockIdx.x) < gfull) {
+    w.first = blockIdx.x;
+    w.end = nfull;
+    w.stride = gfull;
+    w.full = true;
+  } else {
+    w.first = nfull + static_cast<int>(blockIdx.x) - gfull;
+    w.end = ntiles;
+    w.stride = static_cast<int>(gridDim.x) - gfull;
+    w.full = false;
+  }
+  return w;
+}
+
 // --------------------------------------------------------------------- sweep 1 of the round
 // XBAR: 0 = average stays in registers, 1 = also written out, 2 = read from memory instead of
 // being recomputed (dppf_dist_norms with a given x_A).
@@ -239,7 +264,8 @@ __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* 
 }
 
 template <int M, int U, bool SGD, int XBAR, bool NORMS>
-__global__ __launch_bounds__(kBlock) void k_sweep1(const Tile* __restrict__ tiles, int ntiles, int T,
+__global__ __launch_bounds__(kBlock) void k_sweep1(const Tile* __restrict__ tiles, int nfull, int ntiles,
+                                                   int gfull, int T,
                                                    float* const* __restrict__ xp,
                                                    float* const* __restrict__ vp,
                                                    const float* const* __restrict__ gp,
@@ -250,12 +276,13 @@ __global__ __launch_bounds__(kBlock) void k_sweep1(const Tile* __restrict__ tile
 #pragma unroll
   for (int m = 0; m < M; ++m) acc[m] = 0.0;
   const float inv_m = 1.0f / static_cast<float>(M);
-  for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
-    const Tile tl = tiles[t];
-    if (tl.count == kTileElems)
-      sweep1_tile<M, U, SGD, XBAR, NORMS, true>(tl, T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
-    else
-      sweep1_tile<M, U, SGD, XBAR, NORMS, false>(tl, T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
+  const TileWalk w = tile_walk(nfull, ntiles, gfull);
+  if (w.full) {
+    for (int t = w.first; t < w.end; t += w.stride)
+      sweep1_tile<M, U, SGD, XBAR, NORMS, true>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
+  } else {
+    for (int t = w.first; t < w.end; t += w.stride)
+      sweep1_tile<M, U, SGD, XBAR, NORMS, false>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
   }
   if (NORMS) block_sums_store<M>(acc, partials + static_cast<size_t>(blockIdx.x) * pstride);
 }
@@ -394,7 +421,8 @@ __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* 
 // FOLD: the coefficients are derived here from sweep 1's partial sums (no finalize launch);
 // otherwise they are read from `coef`.
 template <int M, int U, int XBAR, bool STEP, bool FOLD>
-__global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tiles, int ntiles, int T,
+__global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tiles, int nfull, int ntiles,
+                                                   int gfull, int T,
                                                    float* const* __restrict__ xp,
                                                    const float* const* __restrict__ vp,
                                                    const float* const* __restrict__ xbarp, float lr,
@@ -402,7 +430,6 @@ __global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tile
                                                    const double* __restrict__ partials, int nparts,
                                                    int pstride, float pull, float push,
                                                    float* __restrict__ r_out, float* __restrict__ c_out) {
-  if (static_cast<int>(blockIdx.x) >= ntiles) return;
   float c[M];
   bool skip[M];
   if (FOLD) {
@@ -414,14 +441,18 @@ __global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tile
       skip[m] = coef[m].skip != 0;
     }
   }
+  const TileWalk w = tile_walk(nfull, ntiles, gfull);
+  if (w.first >= w.end) return;
   // opposite walk order to sweep 1
-  const int last = (ntiles - 1 - static_cast<int>(blockIdx.x)) / static_cast<int>(gridDim.x);
-  for (int j = last; j >= 0; --j) {
-    const Tile tl = tiles[blockIdx.x + j * gridDim.x];
-    if (tl.count == kTileElems)
-      sweep2_tile<M, U, XBAR, STEP, true>(tl, T, xp, vp, xbarp, lr, c, skip, inv_m_total);
-    else
-      sweep2_tile<M, U, XBAR, STEP, false>(tl, T, xp, vp, xbarp, lr, c, skip, inv_m_total);
+  const int last = (w.end - 1 - w.first) / w.stride;
+  if (w.full) {
+    for (int j = last; j >= 0; --j)
+      sweep2_tile<M, U, XBAR, STEP, true>(tiles[w.first + j * w.stride], T, xp, vp, xbarp, lr, c, skip,
+                                          inv_m_total);
+  } else {
+    for (int j = last; j >= 0; --j)
+      sweep2_tile<M, U, XBAR, STEP, false>(tiles[w.first + j * w.stride], T, xp, vp, xbarp, lr, c, skip,
+                                           inv_m_total);
   }
 }
 
@@ -453,20 +484,26 @@ __device__ __forceinline__ void local_tile(float* x, float* v, const float* g, i
 }
 
 template <int U>
-__global__ __launch_bounds__(kBlock) void k_local_step(const Tile* __restrict__ tiles, int ntiles, int M,
-                                                       int T, float* const* __restrict__ xp,
+__global__ __launch_bounds__(kBlock) void k_local_step(const Tile* __restrict__ tiles, int nfull, int ntiles,
+                                                       int gfull, int M, int T,
+                                                       float* const* __restrict__ xp,
                                                        float* const* __restrict__ vp,
                                                        const float* const* __restrict__ gp, float lr,
                                                        float mu, float wd) {
-  const long long total = static_cast<long long>(ntiles) * M;
-  for (long long j = blockIdx.x; j < total; j += gridDim.x) {
-    const int m = static_cast<int>(j / ntiles);
-    const Tile tl = tiles[j - static_cast<long long>(m) * ntiles];
+  // work items are (tile, worker) pairs; blocks [0, gfull) take the full tiles
+  const bool full = static_cast<int>(blockIdx.x) < gfull;
+  const long long base = full ? 0 : nfull;
+  const long long count = full ? nfull : ntiles - nfull;
+  const long long first = full ? blockIdx.x : static_cast<long long>(blockIdx.x) - gfull;
+  const long long stride = full ? gfull : static_cast<long long>(gridDim.x) - gfull;
+  for (long long j = first; j < count * M; j += stride) {
+    const int m = static_cast<int>(j / count);
+    const Tile tl = tiles[base + (j - static_cast<long long>(m) * count)];
     const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
     float* x = xp[slot] + tl.offset;
     float* v = vp[slot] + tl.offset;
     const float* g = gp[slot] + tl.offset;
-    if (tl.count == kTileElems)
+    if (full)
       local_tile<U, true>(x, v, g, tl.count, lr, mu, wd);
     else
       local_tile<U, false>(x, v, g, tl.count, lr, mu, wd);
@@ -488,14 +525,16 @@ __device__ __forceinline__ void mean_any_tile(const Tile tl, int M, int T,
   }
 }
 
-__global__ __launch_bounds__(kBlock) void k_mean_any(const Tile* __restrict__ tiles, int ntiles, int M, int T,
+__global__ __launch_bounds__(kBlock) void k_mean_any(const Tile* __restrict__ tiles, int nfull, int ntiles,
+                                                     int gfull, int M, int T,
                                                      float* const* __restrict__ xp,
                                                      float* const* __restrict__ xbarp) {
   const float inv_m = 1.0f / static_cast<float>(M);
-  for (int t = blockIdx.x; t < ntiles; t += gridDim.x) {
+  const TileWalk w = tile_walk(nfull, ntiles, gfull);
+  for (int t = w.first; t < w.end; t += w.stride) {
     const Tile tl = tiles[t];
     float* xb = xbarp[tl.tensor] + tl.offset;
-    if (tl.count == kTileElems) mean_any_tile<true>(tl, M, T, xp, xb, inv_m);
+    if (w.full) mean_any_tile<true>(tl, M, T, xp, xb, inv_m);
     else mean_any_tile<false>(tl, M, T, xp, xb, inv_m);
   }
 }
@@ -546,6 +585,7 @@ struct dppf_plan {
   long long d = 0;
   std::vector<long long> numel;
   int ntiles = 0;
+  int nfull = 0;                // tiles [0, nfull) are full, [nfull, ntiles) partial
   Tile* tiles_dev = nullptr;
   double* partials = nullptr;   // [max blocks][M]
   int partials_rows = 0;
@@ -631,19 +671,29 @@ int timing_end(dppf_plan* p, hipStream_t s) {
 
 // ---- grid sizes: enough resident blocks to fill every CU, never more blocks than tiles
 template <typename K>
-int grid_for(const dppf_plan* p, K kernel, long long work_items, int want_per_cu, int* grid_out) {
+int grid_for(const dppf_plan* p, K kernel, int per_tile_items, int want_per_cu, int* gfull_out,
+             int* grid_out) {
   int per_cu = 0;
   HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBlock, 0));
   if (per_cu < 1) per_cu = 1;
   if (per_cu > want_per_cu) per_cu = want_per_cu;
-  if (per_cu > kMaxBlocksPerCU) per_cu = kMaxBlocksPerCU;
-  long long g = static_cast<long long>(p->num_cu) * per_cu;
-  if (g > work_items) g = work_items;
-  if (g > p->partials_rows) g = p->partials_rows;
-  if (g < 1) g = 1;
-  *grid_out = static_cast<int>(g);
+  if (per_cu > kMaxBlocksPerCU - 1) per_cu = kMaxBlocksPerCU - 1;
+  // streaming blocks for the full tiles ...
+  long long gfull = static_cast<long long>(p->num_cu) * per_cu;
+  const long long full_items = static_cast<long long>(p->nfull) * per_tile_items;
+  if (gfull > full_items) gfull = full_items;
+  // ... plus up to one more block per CU for the partial tiles
+  long long gpart = p->num_cu;
+  const long long part_items = static_cast<long long>(p->ntiles - p->nfull) * per_tile_items;
+  if (gpart > part_items) gpart = part_items;
+  *gfull_out = static_cast<int>(gfull);
+  *grid_out = static_cast<int>(gfull + gpart);   // <= num_cu * kMaxBlocksPerCU = partials_rows
   return DPPF_OK;
 }
+
+struct GridShape {
+  int gfull = 0, grid = 0;
+};
 
 constexpr int unroll_plain(int M) { return M <= 4 ? 4 : (M <= 8 ? 2 : 1); }   // M*U <= 16 vectors
 constexpr int unroll_step_update(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }   // 2*M*U <= 16 vectors
@@ -665,7 +715,7 @@ constexpr int unroll_fused(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }   //
 // Launch sweep 1 over workers [m0, m0+mg) of the table (mg <= 8).
 template <bool SGD, int XBAR, bool NORMS>
 int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const void** gp,
-                  const void** xbarp, float lr, float mu, float wd, int m0, int* grid_used,
+                  const void** xbarp, float lr, float mu, float wd, int m0, GridShape* shape,
                   hipStream_t s) {
   float* const* x = (float* const*)(xp) + static_cast<size_t>(m0) * p->T;
   float* const* v = vp ? (float* const*)(vp) + static_cast<size_t>(m0) * p->T : nullptr;
@@ -674,14 +724,20 @@ int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const 
   DPPF_SWITCH_M(mg, {
     constexpr int kU = SGD ? unroll_fused(kM) : unroll_plain(kM);
     auto kern = k_sweep1<kM, kU, SGD, XBAR, NORMS>;
-    int grid = 0;
-    int rc = grid_for(p, kern, p->ntiles, (SGD || XBAR == 1) ? kBlocksPerCUReadWrite : kBlocksPerCUReadOnly, &grid);
-    if (rc) return rc;
-    if (grid_used) {
-      if (*grid_used > 0) grid = *grid_used;   // later worker groups must use the same rows
-      *grid_used = grid;
+    int grid = 0, gfull = 0;
+    if (shape && shape->grid > 0) {   // later worker groups must fill the same rows of the partial sums
+      gfull = shape->gfull;
+      grid = shape->grid;
+    } else {
+      int rc = grid_for(p, kern, 1, (SGD || XBAR == 1) ? kBlocksPerCUReadWrite : kBlocksPerCUReadOnly, &gfull,
+                        &grid);
+      if (rc) return rc;
+      if (shape) {
+        shape->gfull = gfull;
+        shape->grid = grid;
+      }
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->ntiles, p->T, x, v, g, xb,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, v, g, xb,
                        lr, mu, wd, p->partials + m0, p->M);
   })
   HIP_TRY(hipGetLastError());
@@ -697,10 +753,10 @@ int launch_sweep2(dppf_plan* p, int mg, const void** xp, const void** vp, const 
   DPPF_SWITCH_M(mg, {
     constexpr int kU = STEP ? unroll_step_update(kM) : unroll_plain(kM);
     auto kern = k_sweep2<kM, kU, XBAR, STEP, FOLD>;
-    int grid = 0;
-    int rc = grid_for(p, kern, p->ntiles, kBlocksPerCUReadWrite, &grid);
+    int grid = 0, gfull = 0;
+    int rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid);
     if (rc) return rc;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->ntiles, p->T, x, v, xb, lr,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, v, xb, lr,
                        p->coef + m0, 1.0f / static_cast<float>(kM), p->partials, nparts, p->M, pull, push,
                        r_out, c_out);
   })
@@ -721,12 +777,12 @@ int launch_finalize(dppf_plan* p, int nparts, float pull, float push, bool want_
 int launch_local_step(dppf_plan* p, const void** xp, const void** vp, const void** gp, float lr,
                       float mu, float wd, hipStream_t s) {
   auto kern = k_local_step<4>;
-  int grid = 0;
-  int rc = grid_for(p, kern, static_cast<long long>(p->ntiles) * p->M, kBlocksPerCUReadWrite, &grid);
+  int grid = 0, gfull = 0;
+  int rc = grid_for(p, kern, p->M, kBlocksPerCUReadWrite, &gfull, &grid);
   if (rc) return rc;
   rc = timing_begin(p, DPPF_K_LOCAL_STEP, s);
   if (rc) return rc;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->ntiles, p->M, p->T,
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M, p->T,
                      (float* const*)(xp), (float* const*)(vp),
                      (const float* const*)(gp), lr, mu, wd);
   HIP_TRY(hipGetLastError());
@@ -734,10 +790,10 @@ int launch_local_step(dppf_plan* p, const void** xp, const void** vp, const void
 }
 
 int launch_mean_any(dppf_plan* p, const void** xp, const void** xbarp, hipStream_t s) {
-  int grid = 0;
-  int rc = grid_for(p, k_mean_any, p->ntiles, kBlocksPerCUReadWrite, &grid);
+  int grid = 0, gfull = 0;
+  int rc = grid_for(p, k_mean_any, 1, kBlocksPerCUReadWrite, &gfull, &grid);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_mean_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->ntiles, p->M, p->T,
+  hipLaunchKernelGGL(k_mean_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M, p->T,
                      (float* const*)(xp), (float* const*)(xbarp));
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
@@ -772,23 +828,23 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
   if (p->ntiles == 0) {   // d == 0: every distance is zero, nothing moves
     return launch_finalize(p, 0, pull, push, true, r_out, c_out, s);
   }
-  int grid = 0;
+  GridShape shape;
   if (p->M <= kMaxTemplM) {
     if ((rc = timing_begin(p, with_step ? DPPF_K_STEP_REDUCE : DPPF_K_REDUCE, s))) return rc;
     if (with_step) {
-      rc = xbar_out ? launch_sweep1<true, 1, true>(p, p->M, xd, vd, gd, xbd, lr, mu, wd, 0, &grid, s)
-                    : launch_sweep1<true, 0, true>(p, p->M, xd, vd, gd, nullptr, lr, mu, wd, 0, &grid, s);
+      rc = xbar_out ? launch_sweep1<true, 1, true>(p, p->M, xd, vd, gd, xbd, lr, mu, wd, 0, &shape, s)
+                    : launch_sweep1<true, 0, true>(p, p->M, xd, vd, gd, nullptr, lr, mu, wd, 0, &shape, s);
     } else {
-      rc = xbar_out ? launch_sweep1<false, 1, true>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, &grid, s)
-                    : launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, &grid, s);
+      rc = xbar_out ? launch_sweep1<false, 1, true>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, &shape, s)
+                    : launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, &shape, s);
     }
     if (rc) return rc;
     if ((rc = timing_end(p, s))) return rc;
     if ((rc = timing_begin(p, (with_step && kDeferStepStore) ? DPPF_K_STEP_UPDATE : DPPF_K_UPDATE, s))) return rc;
     if (with_step && kDeferStepStore)
-      rc = launch_sweep2<0, true, true>(p, p->M, xd, vd, nullptr, lr, 0, grid, pull, push, r_out, c_out, s);
+      rc = launch_sweep2<0, true, true>(p, p->M, xd, vd, nullptr, lr, 0, shape.grid, pull, push, r_out, c_out, s);
     else
-      rc = launch_sweep2<0, false, true>(p, p->M, xd, nullptr, nullptr, 0.f, 0, grid, pull, push, r_out, c_out, s);
+      rc = launch_sweep2<0, false, true>(p, p->M, xd, nullptr, nullptr, 0.f, 0, shape.grid, pull, push, r_out, c_out, s);
     if (rc) return rc;
     return timing_end(p, s);
   }
@@ -803,10 +859,10 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
   if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
   for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
     const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
-    if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, &grid, s))) return rc;
+    if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, &shape, s))) return rc;
   }
   if ((rc = timing_end(p, s))) return rc;
-  if ((rc = launch_finalize(p, grid, pull, push, true, r_out, c_out, s))) return rc;
+  if ((rc = launch_finalize(p, shape.grid, pull, push, true, r_out, c_out, s))) return rc;
   if ((rc = timing_begin(p, DPPF_K_UPDATE, s))) return rc;
   for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
     const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
@@ -878,6 +934,19 @@ int dppf_plan_create(dppf_plan** out, int M, int T, const int64_t* numel) {
   } catch (const std::bad_alloc&) {
     delete p;
     return DPPF_ENOMEM;
+  }
+  {   // full tiles first (list order kept inside each group)
+    std::vector<Tile> ordered;
+    try {
+      ordered.reserve(tiles.size());
+      for (const Tile& t : tiles) if (t.count == kTileElems) ordered.push_back(t);
+      p->nfull = static_cast<int>(ordered.size());
+      for (const Tile& t : tiles) if (t.count != kTileElems) ordered.push_back(t);
+    } catch (const std::bad_alloc&) {
+      delete p;
+      return DPPF_ENOMEM;
+    }
+    tiles.swap(ordered);
   }
   p->ntiles = static_cast<int>(tiles.size());
 
@@ -954,11 +1023,11 @@ int dppf_dist_norms(dppf_plan* p, const float* const* x, const float* const* xba
                                  static_cast<size_t>(p->T), s, &xbd)))
     return rc;
   if (p->ntiles == 0) return launch_finalize(p, 0, 0.f, 0.f, false, r_out, nullptr, s);
-  int grid = 0;
+  GridShape shape;
   if (p->M <= kMaxTemplM) {
     if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
-    rc = xbar ? launch_sweep1<false, 2, true>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, &grid, s)
-              : launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, &grid, s);
+    rc = xbar ? launch_sweep1<false, 2, true>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, &shape, s)
+              : launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, &shape, s);
     if (rc) return rc;
     if ((rc = timing_end(p, s))) return rc;
   } else {
@@ -970,11 +1039,11 @@ int dppf_dist_norms(dppf_plan* p, const float* const* x, const float* const* xba
     if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
     for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
       const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
-      if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, &grid, s))) return rc;
+      if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, &shape, s))) return rc;
     }
     if ((rc = timing_end(p, s))) return rc;
   }
-  return launch_finalize(p, grid, 0.f, 0.f, false, r_out, nullptr, s);
+  return launch_finalize(p, shape.grid, 0.f, 0.f, false, r_out, nullptr, s);
 }
 
 int dppf_pull_push_round(dppf_plan* p, float* const* x, float pull, float push, float* r_out,
