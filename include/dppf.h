@@ -107,6 +107,49 @@ int dppf_round(dppf_plan* plan, float* const* x, float* const* v, const float* c
                float* r_out, float* c_out, float* const* xbar_out, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Variants of the round.
+ * ------------------------------------------------------------------------------------- */
+
+/* The round with the EXACT gradient of the relaxed Inverse-Mean-Valley regulariser, both terms
+ * of Eq. 4 (a) kept (appendix "Ablation Study on the Second Term"):
+ *   d_m = x_m - x_A;  x_m <- x_m - pull d_m + (push_r / M^2) (M d_m/||d_m|| - sum_j d_j/||d_j||).
+ * push_r is the regulariser's own coefficient lambda_r (Eq. 5's lambda corresponds to push_r / M).
+ * Workers at zero distance contribute a zero unit vector.  The average of the workers is
+ * preserved.  r_out[m] = ||d_m||, c_out[m] = pull - (push_r/M)/r_m, both optional.  Same two
+ * sweeps and the same memory traffic as dppf_pull_push_round.  M <= 8 (else DPPF_ELIMIT).  */
+int dppf_pull_push_round_exact(dppf_plan* plan, float* const* x, float pull, float push_r,
+                               float* r_out, float* c_out, void* stream);
+
+/* Alg. 1 taken literally, for ANY consensus variable x_C supplied by the caller (T table, read):
+ *   x_m <- (1 - pull) x_m + pull x_C;  then  x_m <- x_m + push (x_m - ref) / ||x_m - ref||
+ * with the ALREADY PULLED x_m, where ref is the workers' average before the round
+ * (DPPF_PUSH_FROM_AVERAGE, Alg. 1) or x_C itself (DPPF_PUSH_FROM_CONSENSUS, the variant the
+ * appendix remark on leader-based consensus describes).  A worker whose pulled gap is zero gets
+ * no push.  r_post_out[m] (optional) = norm of the pulled gap.  With x_C = x_A and pull < 1 the
+ * result equals dppf_pull_push_round.  M <= 8 (else DPPF_ELIMIT).  */
+enum { DPPF_PUSH_FROM_AVERAGE = 0, DPPF_PUSH_FROM_CONSENSUS = 1 };
+int dppf_pull_then_push(dppf_plan* plan, float* const* x, const float* const* x_c, float pull,
+                        float push, int push_from, float* r_post_out, void* stream);
+
+/* AdamW local step (the optimizer of the ViT experiments, appendix; formula: decoupled weight
+ * decay Adam):  x <- x (1 - lr wd);  m1 <- b1 m1 + (1-b1) g;  m2 <- b2 m2 + (1-b2) g^2;
+ *   x <- x - lr (m1 / (1-b1^step)) / (sqrt(m2 / (1-b2^step)) + eps),   step = 1, 2, ...
+ * x, m1, m2: M*T tables (read+written); g: M*T table (read).  */
+int dppf_local_adamw_step(dppf_plan* plan, float* const* x, float* const* m1, float* const* m2,
+                          const float* const* g, float lr, float beta1, float beta2, float eps,
+                          float weight_decay, int64_t step, void* stream);
+
+/* What the paper logs every round (appendix "Pull-Push Mechanism"), from the distances r (device,
+ * M floats, e.g. r_out of a round):  out[0] = relaxed MV = (1/M) sum_m r_m;
+ * out[1..M] = pull strength pull*r_m;  out[M+1..2M] = push strength push.  out: device, 2M+1 floats. */
+int dppf_round_statistics(const float* r, int M, float pull, float push, float* out, void* stream);
+
+/* Push-strength schedules (appendix "How to Schedule The Pushing Force?"), a HOST function:
+ * fixed: push;  decreasing: (push/2)(1 + cos(pi t/t_total));  increasing: (push/2)(1 - cos(pi t/t_total)). */
+enum { DPPF_SCHEDULE_FIXED = 0, DPPF_SCHEDULE_DECREASING = 1, DPPF_SCHEDULE_INCREASING = 2 };
+float dppf_push_schedule(int kind, float push, int64_t t, int64_t t_total);
+
+/* ---------------------------------------------------------------------------------------
  * Flat convenience forms for a plan made with T == 1: worker m's vector starts at
  * x + m*ld (ld >= d elements).  Same semantics as the table forms above.
  * ------------------------------------------------------------------------------------- */
@@ -133,7 +176,11 @@ enum {
   DPPF_K_UPDATE = 3,       /* sweep 2 of the round: Eq. 5                                */
   DPPF_K_LOCAL_STEP = 4,   /* stand-alone local step                                     */
   DPPF_K_MEAN = 5,         /* stand-alone average                                        */
-  DPPF_K_STEP_UPDATE = 6   /* sweep 2 of the fused round: x - lr v rebuilt, then Eq. 5   */
+  DPPF_K_STEP_UPDATE = 6,  /* sweep 2 of the fused round: x - lr v rebuilt, then Eq. 5   */
+  DPPF_K_UPDATE_EXACT = 7, /* sweep 2 with the two-term gradient                         */
+  DPPF_K_SEQ_REDUCE = 8,   /* dppf_pull_then_push, sweep 1                               */
+  DPPF_K_SEQ_UPDATE = 9,   /* dppf_pull_then_push, sweep 2                               */
+  DPPF_K_ADAMW_STEP = 10   /* AdamW local step                                           */
 };
 int dppf_plan_timing_enable(dppf_plan* plan, int enable);
 int dppf_plan_timing_read(dppf_plan* plan, int* kernel_id, float* ms, int cap);

@@ -19,6 +19,7 @@
 //     sweep 1 touched last is still in the last-level cache when sweep 2 starts.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
@@ -324,10 +325,12 @@ template <int M>
 __device__ __forceinline__ void coefficients_from_partials(const double* __restrict__ partials, int nparts,
                                                            int pstride, float pull, float push,
                                                            float (&c)[M], bool (&skip)[M],
+                                                           float (&inv_r)[M],
                                                            float* __restrict__ r_out,
                                                            float* __restrict__ c_out) {
   __shared__ double lds[kBlock / 64][M];
   __shared__ float c_sh[M];
+  __shared__ float inv_sh[M];
   __shared__ int skip_sh[M];
   double acc[M];
 #pragma unroll
@@ -352,6 +355,7 @@ __device__ __forceinline__ void coefficients_from_partials(const double* __restr
     const double cc = zero ? static_cast<double>(pull)
                            : static_cast<double>(pull) - static_cast<double>(push) / r;
     c_sh[threadIdx.x] = static_cast<float>(cc);
+    inv_sh[threadIdx.x] = zero ? 0.f : static_cast<float>(1.0 / r);
     skip_sh[threadIdx.x] = zero ? 1 : 0;
     if (blockIdx.x == 0) {
       if (r_out) r_out[threadIdx.x] = static_cast<float>(r);
@@ -362,6 +366,7 @@ __device__ __forceinline__ void coefficients_from_partials(const double* __restr
 #pragma unroll
   for (int m = 0; m < M; ++m) {
     c[m] = c_sh[m];
+    inv_r[m] = inv_sh[m];
     skip[m] = skip_sh[m] != 0;
   }
 }
@@ -433,7 +438,8 @@ __global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tile
   float c[M];
   bool skip[M];
   if (FOLD) {
-    coefficients_from_partials<M>(partials, nparts, pstride, pull, push, c, skip, r_out, c_out);
+    float inv_r[M];
+    coefficients_from_partials<M>(partials, nparts, pstride, pull, push, c, skip, inv_r, r_out, c_out);
   } else {
 #pragma unroll
     for (int m = 0; m < M; ++m) {
@@ -453,6 +459,247 @@ __global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tile
     for (int j = last; j >= 0; --j)
       sweep2_tile<M, U, XBAR, STEP, false>(tiles[w.first + j * w.stride], T, xp, vp, xbarp, lr, c, skip,
                                            inv_m_total);
+  }
+}
+
+// ------------------------------------------------ sweep 2 with the exact two-term gradient
+// Eq. 4 (a): x_m <- x_m - alpha d_m + (lambda_r / M^2) (M d_m/r_m - sum_j d_j/r_j), d = x - x_A.
+// With gap = x_A - x (= -d):  x_m + gap_m (alpha - (lambda_r/M)/r_m) + (lambda_r/M^2) sum_j gap_j/r_j.
+// All M replicas of an element are in registers here, so the sum over j costs no memory traffic.
+// Workers at zero distance contribute a zero unit vector (1/r_j := 0) but still receive the sum.
+template <int M, int U, bool FULL>
+__device__ __forceinline__ void exact_tile(const Tile tl, int T, float* const* __restrict__ xp,
+                                           const float (&c)[M], const float (&inv_r)[M], float k2,
+                                           float inv_m) {
+  float* x[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) x[m] = xp[m * T + tl.tensor] + tl.offset;
+#pragma unroll 1
+  for (int it = 0; it < kVecPerThread / U; ++it) {
+    int e[U], n[U];
+    f4 xv[U][M];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      e[k] = 4 * (threadIdx.x + (it * U + k) * kBlock);
+      n[k] = FULL ? 4 : tl.count - e[k];
+#pragma unroll
+      for (int m = 0; m < M; ++m) xv[k][m] = load4_stream<FULL>(x[m] + e[k], n[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      const f4 xbar = mean_of<M>(xv[k], inv_m);
+      f4 usum = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int m = 0; m < M; ++m) usum = fma4(xbar - xv[k][m], inv_r[m], usum);
+#pragma unroll
+      for (int m = 0; m < M; ++m) {
+        f4 moved = fma4(xbar - xv[k][m], c[m], xv[k][m]);
+        moved = fma4(usum, k2, moved);
+        store4_stream<FULL>(x[m] + e[k], moved, n[k]);
+      }
+    }
+  }
+}
+
+template <int M, int U>
+__global__ __launch_bounds__(kBlock) void k_update_exact(const Tile* __restrict__ tiles, int nfull, int ntiles,
+                                                         int gfull, int T, float* const* __restrict__ xp,
+                                                         const double* __restrict__ partials, int nparts,
+                                                         int pstride, float pull, float push_over_m, float k2,
+                                                         float* __restrict__ r_out, float* __restrict__ c_out) {
+  float c[M], inv_r[M];
+  bool skip[M];
+  coefficients_from_partials<M>(partials, nparts, pstride, pull, push_over_m, c, skip, inv_r, r_out, c_out);
+  const float inv_m = 1.0f / static_cast<float>(M);
+  const TileWalk w = tile_walk(nfull, ntiles, gfull);
+  if (w.first >= w.end) return;
+  const int last = (w.end - 1 - w.first) / w.stride;
+  if (w.full) {
+    for (int j = last; j >= 0; --j) exact_tile<M, U, true>(tiles[w.first + j * w.stride], T, xp, c, inv_r, k2, inv_m);
+  } else {
+    for (int j = last; j >= 0; --j) exact_tile<M, U, false>(tiles[w.first + j * w.stride], T, xp, c, inv_r, k2, inv_m);
+  }
+}
+
+// ------------------------------------------- Alg. 1 written literally, any consensus variable
+// pulled_m = (1 - alpha) x_m + alpha x_C; gap_m = pulled_m - ref (ref = x_A before the round, or x_C);
+// r_m = ||gap_m||; x_m <- pulled_m + lambda gap_m / r_m  (no push where r_m = 0).
+// REF: 0 = push away from the average, 1 = push away from the consensus variable.
+template <int M, int U, int REF, bool WRITE, bool FULL>
+__device__ __forceinline__ void seq_tile(const Tile tl, int T, float* const* __restrict__ xp,
+                                         const float* const* __restrict__ xcp, float pull, float keep,
+                                         const float (&scale)[M], float inv_m, double (&acc)[M]) {
+  float* x[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) x[m] = xp[m * T + tl.tensor] + tl.offset;
+  const float* xc = xcp[tl.tensor] + tl.offset;
+  float part[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) part[m] = 0.f;
+#pragma unroll 1
+  for (int it = 0; it < kVecPerThread / U; ++it) {
+    int e[U], n[U];
+    f4 xv[U][M], cv[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      e[k] = 4 * (threadIdx.x + (it * U + k) * kBlock);
+      n[k] = FULL ? 4 : tl.count - e[k];
+      cv[k] = load4<FULL>(xc + e[k], n[k]);
+#pragma unroll
+      for (int m = 0; m < M; ++m)
+        xv[k][m] = WRITE ? load4_stream<FULL>(x[m] + e[k], n[k]) : load4<FULL>(x[m] + e[k], n[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      const f4 ref = (REF == 0) ? mean_of<M>(xv[k], inv_m) : cv[k];
+#pragma unroll
+      for (int m = 0; m < M; ++m) {
+        const f4 pulled = fma4(cv[k], pull, xv[k][m] * keep);   // (1-alpha) x + alpha x_C: exactly x_C at alpha = 1
+        const f4 gap = pulled - ref;
+        if (WRITE) store4_stream<FULL>(x[m] + e[k], fma4(gap, scale[m], pulled), n[k]);
+        else part[m] = sumsq4(gap, part[m]);
+      }
+    }
+  }
+  if (!WRITE) {
+#pragma unroll
+    for (int m = 0; m < M; ++m) acc[m] += static_cast<double>(part[m]);
+  }
+}
+
+template <int M, int U, int REF>
+__global__ __launch_bounds__(kBlock) void k_seq1(const Tile* __restrict__ tiles, int nfull, int ntiles, int gfull,
+                                                 int T, float* const* __restrict__ xp,
+                                                 const float* const* __restrict__ xcp, float pull, float keep,
+                                                 double* __restrict__ partials, int pstride) {
+  double acc[M];
+  float scale[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) {
+    acc[m] = 0.0;
+    scale[m] = 0.f;
+  }
+  const float inv_m = 1.0f / static_cast<float>(M);
+  const TileWalk w = tile_walk(nfull, ntiles, gfull);
+  if (w.full) {
+    for (int t = w.first; t < w.end; t += w.stride)
+      seq_tile<M, U, REF, false, true>(tiles[t], T, xp, xcp, pull, keep, scale, inv_m, acc);
+  } else {
+    for (int t = w.first; t < w.end; t += w.stride)
+      seq_tile<M, U, REF, false, false>(tiles[t], T, xp, xcp, pull, keep, scale, inv_m, acc);
+  }
+  block_sums_store<M>(acc, partials + static_cast<size_t>(blockIdx.x) * pstride);
+}
+
+template <int M, int U, int REF>
+__global__ __launch_bounds__(kBlock) void k_seq2(const Tile* __restrict__ tiles, int nfull, int ntiles, int gfull,
+                                                 int T, float* const* __restrict__ xp,
+                                                 const float* const* __restrict__ xcp, float pull, float keep,
+                                                 float push, const double* __restrict__ partials, int nparts,
+                                                 int pstride, float* __restrict__ r_post_out) {
+  // lambda / r_m from the partial sums (c = 0 - push/r, so scale = -c; zero distance: no push)
+  float c[M], scale[M], inv_r[M];
+  bool skip[M];
+  coefficients_from_partials<M>(partials, nparts, pstride, 0.f, push, c, skip, inv_r, r_post_out, nullptr);
+#pragma unroll
+  for (int m = 0; m < M; ++m) scale[m] = skip[m] ? 0.f : -c[m];
+  double unused[M];
+  const float inv_m = 1.0f / static_cast<float>(M);
+  const TileWalk w = tile_walk(nfull, ntiles, gfull);
+  if (w.first >= w.end) return;
+  const int last = (w.end - 1 - w.first) / w.stride;
+  if (w.full) {
+    for (int j = last; j >= 0; --j)
+      seq_tile<M, U, REF, true, true>(tiles[w.first + j * w.stride], T, xp, xcp, pull, keep, scale, inv_m, unused);
+  } else {
+    for (int j = last; j >= 0; --j)
+      seq_tile<M, U, REF, true, false>(tiles[w.first + j * w.stride], T, xp, xcp, pull, keep, scale, inv_m, unused);
+  }
+}
+
+// ------------------------------------------------------------------ AdamW local step
+// Decoupled weight decay Adam: x <- x (1 - lr wd); m <- b1 m + (1-b1) g; s <- b2 s + (1-b2) g^2;
+// x <- x - lr (m / bc1) / (sqrt(s / bc2) + eps), bc_i = 1 - b_i^t computed on the host.
+template <int U, bool FULL>
+__device__ __forceinline__ void adamw_tile(float* x, float* m1, float* m2, const float* g, int count, float lr,
+                                           float b1, float b2, float eps, float wd, float inv_bc1,
+                                           float inv_bc2) {
+#pragma unroll 1
+  for (int it = 0; it < kVecPerThread / U; ++it) {
+    int e[U], n[U];
+    f4 xv[U], av[U], sv[U], gv[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      e[k] = 4 * (threadIdx.x + (it * U + k) * kBlock);
+      n[k] = FULL ? 4 : count - e[k];
+      xv[k] = load4_stream<FULL>(x + e[k], n[k]);
+      av[k] = load4_stream<FULL>(m1 + e[k], n[k]);
+      sv[k] = load4_stream<FULL>(m2 + e[k], n[k]);
+      gv[k] = load4_stream<FULL>(g + e[k], n[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      f4 xn, an, sn;
+      const float* xs = reinterpret_cast<const float*>(&xv[k]);
+      const float* as = reinterpret_cast<const float*>(&av[k]);
+      const float* ss = reinterpret_cast<const float*>(&sv[k]);
+      const float* gs = reinterpret_cast<const float*>(&gv[k]);
+      float* xo = reinterpret_cast<float*>(&xn);
+      float* ao = reinterpret_cast<float*>(&an);
+      float* so = reinterpret_cast<float*>(&sn);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float xd = __builtin_fmaf(-lr * wd, xs[i], xs[i]);
+        const float a = __builtin_fmaf(b1, as[i], (1.0f - b1) * gs[i]);
+        const float q = __builtin_fmaf(b2, ss[i], (1.0f - b2) * gs[i] * gs[i]);
+        const float denom = __builtin_sqrtf(q * inv_bc2) + eps;
+        xo[i] = xd - lr * (a * inv_bc1) / denom;
+        ao[i] = a;
+        so[i] = q;
+      }
+      store4_stream<FULL>(m1 + e[k], an, n[k]);
+      store4_stream<FULL>(m2 + e[k], sn, n[k]);
+      store4_stream<FULL>(x + e[k], xn, n[k]);
+    }
+  }
+}
+
+template <int U>
+__global__ __launch_bounds__(kBlock) void k_adamw_step(const Tile* __restrict__ tiles, int nfull, int ntiles,
+                                                       int gfull, int M, int T, float* const* __restrict__ xp,
+                                                       float* const* __restrict__ ap, float* const* __restrict__ sp,
+                                                       const float* const* __restrict__ gp, float lr, float b1,
+                                                       float b2, float eps, float wd, float inv_bc1,
+                                                       float inv_bc2) {
+  const bool full = static_cast<int>(blockIdx.x) < gfull;
+  const long long base = full ? 0 : nfull;
+  const long long count = full ? nfull : ntiles - nfull;
+  const long long first = full ? blockIdx.x : static_cast<long long>(blockIdx.x) - gfull;
+  const long long stride = full ? gfull : static_cast<long long>(gridDim.x) - gfull;
+  for (long long j = first; j < count * M; j += stride) {
+    const int m = static_cast<int>(j / count);
+    const Tile tl = tiles[base + (j - static_cast<long long>(m) * count)];
+    const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
+    float* x = xp[slot] + tl.offset;
+    float* a = ap[slot] + tl.offset;
+    float* q = sp[slot] + tl.offset;
+    const float* g = gp[slot] + tl.offset;
+    if (full) adamw_tile<U, true>(x, a, q, g, tl.count, lr, b1, b2, eps, wd, inv_bc1, inv_bc2);
+    else adamw_tile<U, false>(x, a, q, g, tl.count, lr, b1, b2, eps, wd, inv_bc1, inv_bc2);
+  }
+}
+
+// ------------------------------------------------ by-products the paper logs every round
+// out[0] = relaxed MV = (1/M) sum r_m; out[1..M] = pull strength alpha r_m; out[M+1..2M] = lambda.
+__global__ void k_round_stats(const float* __restrict__ r, int M, float pull, float push, float* __restrict__ out) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    double s = 0.0;
+    for (int m = 0; m < M; ++m) s += static_cast<double>(r[m]);
+    out[0] = static_cast<float>(s / M);
+  }
+  for (int m = threadIdx.x; m < M; m += blockDim.x) {
+    out[1 + m] = pull * r[m];
+    out[1 + M + m] = push;
   }
 }
 
@@ -592,7 +839,7 @@ struct dppf_plan {
   Coef* coef = nullptr;         // [M]
   float* xbar_scratch = nullptr;            // d floats, only when M > kMaxTemplM
   std::vector<long long> tensor_offset;     // start of tensor t inside xbar_scratch
-  enum Role { RX = 0, RV, RG, RXBAR, RXBAR_SCRATCH, NROLES };
+  enum Role { RX = 0, RV, RG, RM1, RM2, RXBAR, RXBAR_SCRATCH, RXC, NROLES };
   PtrTable tab[NROLES];
   // timing
   bool timing = false;
@@ -799,6 +1046,51 @@ int launch_mean_any(dppf_plan* p, const void** xp, const void** xbarp, hipStream
   return DPPF_OK;
 }
 
+int launch_update_exact(dppf_plan* p, const void** xp, int nparts, float pull, float push_r, float* r_out,
+                        float* c_out, hipStream_t s) {
+  float* const* x = (float* const*)(xp);
+  const float mf = static_cast<float>(p->M);
+  DPPF_SWITCH_M(p->M, {
+    constexpr int kU = unroll_plain(kM);
+    auto kern = k_update_exact<kM, kU>;
+    int grid = 0, gfull = 0;
+    int rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid);
+    if (rc) return rc;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x,
+                       p->partials, nparts, p->M, pull, push_r / mf, push_r / (mf * mf), r_out, c_out);
+  })
+  HIP_TRY(hipGetLastError());
+  return DPPF_OK;
+}
+
+template <int REF>
+int launch_seq(dppf_plan* p, const void** xp, const void** xcp, float pull, float push, float* r_post_out,
+               hipStream_t s) {
+  float* const* x = (float* const*)(xp);
+  const float* const* xc = (const float* const*)(xcp);
+  const float keep = static_cast<float>(1.0 - static_cast<double>(pull));
+  int rc;
+  DPPF_SWITCH_M(p->M, {
+    constexpr int kU = unroll_plain(kM) > 2 ? 2 : unroll_plain(kM);
+    auto k1 = k_seq1<kM, kU, REF>;
+    auto k2 = k_seq2<kM, kU, REF>;
+    int grid = 0, gfull = 0;
+    if ((rc = grid_for(p, k1, 1, kBlocksPerCUReadOnly, &gfull, &grid))) return rc;
+    if ((rc = timing_begin(p, DPPF_K_SEQ_REDUCE, s))) return rc;
+    hipLaunchKernelGGL(k1, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, xc,
+                       pull, keep, p->partials, p->M);
+    if ((rc = timing_end(p, s))) return rc;
+    const int nparts = grid;
+    if ((rc = grid_for(p, k2, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
+    if ((rc = timing_begin(p, DPPF_K_SEQ_UPDATE, s))) return rc;
+    hipLaunchKernelGGL(k2, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, xc,
+                       pull, keep, push, p->partials, nparts, p->M, r_post_out);
+    if ((rc = timing_end(p, s))) return rc;
+  })
+  HIP_TRY(hipGetLastError());
+  return DPPF_OK;
+}
+
 // The scratch average used when M > 8: a pointer table into the plan's own d-vector.
 int scratch_xbar_table(dppf_plan* p, hipStream_t s, const void*** dev_out) {
   std::vector<const void*> host(static_cast<size_t>(p->T));
@@ -975,7 +1267,7 @@ int dppf_plan_create(dppf_plan** out, int M, int T, const int64_t* numel) {
     PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->xbar_scratch), static_cast<size_t>(p->d) * sizeof(float)));
   const size_t n = static_cast<size_t>(M) * T;
   for (int r = 0; r < dppf_plan::NROLES; ++r) {
-    const bool per_model = (r == dppf_plan::RXBAR || r == dppf_plan::RXBAR_SCRATCH);
+    const bool per_model = (r == dppf_plan::RXBAR || r == dppf_plan::RXBAR_SCRATCH || r == dppf_plan::RXC);
     if (table_alloc(p->tab[r], per_model ? static_cast<size_t>(T) : n) != DPPF_OK) {
       dppf_plan_destroy(p);
       return DPPF_EHIP;
@@ -1071,6 +1363,89 @@ int dppf_round(dppf_plan* p, float* const* x, float* const* v, const float* cons
                float* const* xbar_out, void* stream) {
   return round_impl(p, true, x, v, g, lr, momentum, weight_decay, pull, push, r_out, c_out, xbar_out,
                     static_cast<hipStream_t>(stream));
+}
+
+int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float push_r, float* r_out,
+                               float* c_out, void* stream) {
+  if (!p || !x) return DPPF_EINVAL;
+  if (p->M > kMaxTemplM) return DPPF_ELIMIT;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const void** xd = nullptr;
+  int rc;
+  if ((rc = table_upload(p, dppf_plan::RX, reinterpret_cast<const void* const*>(x),
+                         static_cast<size_t>(p->M) * p->T, s, &xd)))
+    return rc;
+  if (p->ntiles == 0) return launch_finalize(p, 0, pull, push_r / static_cast<float>(p->M), false, r_out, c_out, s);
+  GridShape shape;
+  if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
+  if ((rc = launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, &shape, s))) return rc;
+  if ((rc = timing_end(p, s))) return rc;
+  if ((rc = timing_begin(p, DPPF_K_UPDATE_EXACT, s))) return rc;
+  if ((rc = launch_update_exact(p, xd, shape.grid, pull, push_r, r_out, c_out, s))) return rc;
+  return timing_end(p, s);
+}
+
+int dppf_pull_then_push(dppf_plan* p, float* const* x, const float* const* x_c, float pull, float push,
+                        int push_from, float* r_post_out, void* stream) {
+  if (!p || !x || !x_c || (push_from != DPPF_PUSH_FROM_AVERAGE && push_from != DPPF_PUSH_FROM_CONSENSUS))
+    return DPPF_EINVAL;
+  if (p->M > kMaxTemplM) return DPPF_ELIMIT;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const void **xd = nullptr, **xcd = nullptr;
+  int rc;
+  if ((rc = table_upload(p, dppf_plan::RX, reinterpret_cast<const void* const*>(x),
+                         static_cast<size_t>(p->M) * p->T, s, &xd)))
+    return rc;
+  if ((rc = table_upload(p, dppf_plan::RXC, reinterpret_cast<const void* const*>(x_c),
+                         static_cast<size_t>(p->T), s, &xcd)))
+    return rc;
+  if (p->ntiles == 0) return launch_finalize(p, 0, 0.f, 0.f, false, r_post_out, nullptr, s);
+  return push_from == DPPF_PUSH_FROM_AVERAGE ? launch_seq<0>(p, xd, xcd, pull, push, r_post_out, s)
+                                             : launch_seq<1>(p, xd, xcd, pull, push, r_post_out, s);
+}
+
+int dppf_local_adamw_step(dppf_plan* p, float* const* x, float* const* m1, float* const* m2,
+                          const float* const* g, float lr, float beta1, float beta2, float eps,
+                          float weight_decay, int64_t step, void* stream) {
+  if (!p || !x || !m1 || !m2 || !g || step < 1) return DPPF_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t n = static_cast<size_t>(p->M) * p->T;
+  const void **xd = nullptr, **ad = nullptr, **sd = nullptr, **gd = nullptr;
+  int rc;
+  if ((rc = table_upload(p, dppf_plan::RX, reinterpret_cast<const void* const*>(x), n, s, &xd))) return rc;
+  if ((rc = table_upload(p, dppf_plan::RM1, reinterpret_cast<const void* const*>(m1), n, s, &ad))) return rc;
+  if ((rc = table_upload(p, dppf_plan::RM2, reinterpret_cast<const void* const*>(m2), n, s, &sd))) return rc;
+  if ((rc = table_upload(p, dppf_plan::RG, reinterpret_cast<const void* const*>(g), n, s, &gd))) return rc;
+  if (p->ntiles == 0) return DPPF_OK;
+  // bias corrections 1 - beta^t in double on the host
+  const double bc1 = 1.0 - std::pow(static_cast<double>(beta1), static_cast<double>(step));
+  const double bc2 = 1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(step));
+  auto kern = k_adamw_step<2>;
+  int grid = 0, gfull = 0;
+  if ((rc = grid_for(p, kern, p->M, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
+  if ((rc = timing_begin(p, DPPF_K_ADAMW_STEP, s))) return rc;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M, p->T,
+                     (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), lr,
+                     beta1, beta2, eps, weight_decay, static_cast<float>(1.0 / bc1), static_cast<float>(1.0 / bc2));
+  HIP_TRY(hipGetLastError());
+  return timing_end(p, s);
+}
+
+int dppf_round_statistics(const float* r, int M, float pull, float push, float* out, void* stream) {
+  if (!r || !out || M < 1 || M > DPPF_MAX_WORKERS) return DPPF_EINVAL;
+  hipLaunchKernelGGL(k_round_stats, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), r, M, pull, push, out);
+  HIP_TRY(hipGetLastError());
+  return DPPF_OK;
+}
+
+float dppf_push_schedule(int kind, float push, int64_t t, int64_t t_total) {
+  const double kPi = 3.14159265358979323846;
+  const double frac = (t_total > 0) ? static_cast<double>(t) / static_cast<double>(t_total) : 0.0;
+  switch (kind) {
+    case DPPF_SCHEDULE_DECREASING: return static_cast<float>(0.5 * push * (1.0 + std::cos(kPi * frac)));
+    case DPPF_SCHEDULE_INCREASING: return static_cast<float>(0.5 * push * (1.0 - std::cos(kPi * frac)));
+    default: return push;
+  }
 }
 
 // ---- flat forms (T == 1): build the M-entry tables on the stack of the call

@@ -14,7 +14,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "li
 _lib = None
 
 KERNEL_NAMES = {0: "reduce", 1: "step_reduce", 2: "finalize", 3: "update", 4: "local_step", 5: "mean",
-                6: "step_update"}
+                6: "step_update", 7: "update_exact", 8: "seq_reduce", 9: "seq_update", 10: "adamw_step"}
 
 
 class DppfError(RuntimeError):
@@ -50,6 +50,11 @@ def load():
         "dppf_pull_push_round_flat": (ctypes.c_int, [vp, vp, i64, f, f, vp, vp, vp, vp]),
         "dppf_local_sgd_step_flat": (ctypes.c_int, [vp, vp, vp, vp, i64, f, f, f, vp]),
         "dppf_round_flat": (ctypes.c_int, [vp, vp, vp, vp, i64, f, f, f, f, f, vp, vp, vp, vp]),
+        "dppf_pull_push_round_exact": (ctypes.c_int, [vp, c_fpp, f, f, vp, vp, vp]),
+        "dppf_pull_then_push": (ctypes.c_int, [vp, c_fpp, c_fpp, f, f, ctypes.c_int, vp, vp]),
+        "dppf_local_adamw_step": (ctypes.c_int, [vp, c_fpp, c_fpp, c_fpp, c_fpp, f, f, f, f, f, i64, vp]),
+        "dppf_round_statistics": (ctypes.c_int, [vp, ctypes.c_int, f, f, vp, vp]),
+        "dppf_push_schedule": (f, [ctypes.c_int, f, i64, i64]),
         "dppf_util_copy": (ctypes.c_int, [vp, vp, i64, vp]),
         "dppf_plan_timing_enable": (ctypes.c_int, [vp, ctypes.c_int]),
         "dppf_plan_timing_read": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(f), ctypes.c_int]),
@@ -187,6 +192,27 @@ class Plan:
         _check(self._lib.dppf_round(self._h, x.ptr, v.ptr, g.ptr, lr, momentum, weight_decay, pull, push,
                                     _dev(r_out), _dev(c_out), _tptr(xbar_out), _stream(stream)), "dppf_round")
 
+    # ---- variants of the round and of the local step
+    def pull_push_round_exact(self, x, pull, push_r, r_out=None, c_out=None, stream=None) -> None:
+        x = _table(x)
+        self._expect(x, self.M * self.T, "x")
+        _check(self._lib.dppf_pull_push_round_exact(self._h, x.ptr, pull, push_r, _dev(r_out), _dev(c_out),
+                                                    _stream(stream)), "dppf_pull_push_round_exact")
+
+    def pull_then_push(self, x, x_c, pull, push, push_from="average", r_post_out=None, stream=None) -> None:
+        x, x_c = _table(x), _table(x_c)
+        self._expect(x, self.M * self.T, "x"); self._expect(x_c, self.T, "x_c")
+        code = {"average": 0, "consensus": 1}[push_from]
+        _check(self._lib.dppf_pull_then_push(self._h, x.ptr, x_c.ptr, pull, push, code, _dev(r_post_out),
+                                             _stream(stream)), "dppf_pull_then_push")
+
+    def local_adamw_step(self, x, m1, m2, g, lr, beta1, beta2, eps, weight_decay, step, stream=None) -> None:
+        x, m1, m2, g = _table(x), _table(m1), _table(m2), _table(g)
+        for tab, name in ((x, "x"), (m1, "m1"), (m2, "m2"), (g, "g")):
+            self._expect(tab, self.M * self.T, name)
+        _check(self._lib.dppf_local_adamw_step(self._h, x.ptr, m1.ptr, m2.ptr, g.ptr, lr, beta1, beta2, eps,
+                                               weight_decay, step, _stream(stream)), "dppf_local_adamw_step")
+
     # ---- flat forms (T == 1); x, v, g are [M, ld] tensors or raw device addresses
     def pull_push_round_flat(self, x, ld, pull, push, r_out=None, c_out=None, xbar_out=None, stream=None):
         _check(self._lib.dppf_pull_push_round_flat(self._h, _dev(x), ld, pull, push, _dev(r_out), _dev(c_out),
@@ -217,3 +243,16 @@ class Plan:
 def util_copy(dst, src, n: int, stream=None) -> None:
     """Plain device copy of n floats through the library's load/store path (measurement aid)."""
     _check(load().dppf_util_copy(_dev(dst), _dev(src), n, _stream(stream)), "dppf_util_copy")
+
+
+def round_statistics(r, M: int, pull: float, push: float, out, stream=None) -> None:
+    """out[0] = mean distance, out[1..M] = pull strengths, out[M+1..2M] = push strength (device)."""
+    _check(load().dppf_round_statistics(_dev(r), M, pull, push, _dev(out), _stream(stream)),
+           "dppf_round_statistics")
+
+
+SCHEDULES = {"fixed": 0, "decreasing": 1, "increasing": 2}
+
+
+def push_schedule(kind: str, push: float, t: int, t_total: int) -> float:
+    return float(load().dppf_push_schedule(SCHEDULES[kind], push, t, t_total))

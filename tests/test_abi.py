@@ -75,3 +75,15 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(dppf, "_LIB_PATH", str(tmp_path / "libdppf.so"))
     with pytest.raises(dppf.DppfError):
         dppf.load()
+
+
+def test_push_schedule_is_a_host_function(lib):
+    import math
+    assert lib.dppf_push_schedule(0, 0.5, 3, 10) == 0.5
+    assert abs(lib.dppf_push_schedule(1, 0.5, 5, 10) - 0.25) < 1e-7
+    assert abs(lib.dppf_push_schedule(2, 0.5, 10, 10) - 0.5) < 1e-7
+    assert abs(lib.dppf_push_schedule(2, 0.5, 25, 100) - 0.25 * (1 - math.sqrt(0.5))) < 1e-7
+    assert lib.dppf_round_statistics(None, 4, 0.1, 0.1, None, None) == -1
+    assert lib.dppf_pull_then_push(None, None, None, 0.1, 0.1, 0, None, None) == -1
+    assert lib.dppf_pull_push_round_exact(None, None, 0.1, 0.1, None, None, None) == -1
+    assert lib.dppf_local_adamw_step(None, None, None, None, None, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == -1
