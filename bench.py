@@ -31,8 +31,13 @@ BYTES_PER_RP = {
     "update": 8.0,              # read x, write x
     "local_step": 20.0,         # read x, v, g; write x, v
     "finalize": 0.0,
+    "update_exact": 8.0,        # read x, write x (the sum of unit vectors is formed in registers)
+    "seq_reduce": None,         # read x and x_C: 4 + 4/M
+    "seq_update": None,         # read x and x_C, write x: 8 + 4/M
+    "adamw_step": 28.0,         # read x, m1, m2, g; write x, m1, m2
 }
-CALL_BYTES = {"round": 28.0, "pull_push": 12.0, "local_step": 20.0}
+CALL_BYTES = {"round": 28.0, "pull_push": 12.0, "local_step": 20.0, "pull_push_exact": 12.0,
+              "pull_then_push": None, "adamw_step": 28.0}       # None: depends on M, see below
 
 
 def kernel_source_hash() -> str:
@@ -55,7 +60,8 @@ def measured_traffic(kernel: str, workload: str):
 
 def cpu_baseline(spec, inp, g_host, hyper, sample_cols: int):
     """The CPU oracle as it stands, timed on a bounded sample of the same workload: the first
-    `sample_cols` coordinates of every worker (one local step + one round, float64)."""
+    `sample_cols` coordinates of every worker (one local step + one round, float64).  Whatever
+    --call is benchmarked, this leg always times the fused round's oracle."""
     import numpy as np
     from oracle import dppf_oracle as O
     n = min(sample_cols, spec.d)
@@ -109,10 +115,23 @@ def main() -> int:
         return out
 
     x, v, g = rows(inp.x), rows(inp.v), rows(g_host)
+    bytes_per_rp = dict(BYTES_PER_RP)
+    bytes_per_rp["seq_reduce"] = 4.0 + 4.0 / spec.M
+    bytes_per_rp["seq_update"] = 8.0 + 4.0 / spec.M
+    call_bytes = dict(CALL_BYTES)
+    call_bytes["pull_then_push"] = 12.0 + 8.0 / spec.M
+    if args.call == "adamw_step":
+        m2 = rows(inp.v)
+    if args.call == "pull_then_push":
+        xc = [torch.from_numpy(inp.x[0][inp.offsets[t]:inp.offsets[t + 1]]).to("cuda") for t in range(spec.T)]
+        xct = dppf.PointerTable(xc)
     r = torch.zeros(spec.M, device="cuda")
     c = torch.zeros(spec.M, device="cuda")
     plan = dppf.Plan(spec.M, spec.numel)
     xt, vt, gt = dppf.PointerTable(x), dppf.PointerTable(v), dppf.PointerTable(g)
+
+    state = {"t": 0}
+    m2t = dppf.PointerTable(m2) if args.call == "adamw_step" else None
 
     def step():
         if args.call == "round":
@@ -120,6 +139,13 @@ def main() -> int:
                        c_out=c)
         elif args.call == "pull_push":
             plan.pull_push_round(xt, hyper["pull"], hyper["push"], r_out=r, c_out=c)
+        elif args.call == "pull_push_exact":
+            plan.pull_push_round_exact(xt, hyper["pull"], hyper["push"] * spec.M, r_out=r, c_out=c)
+        elif args.call == "pull_then_push":
+            plan.pull_then_push(xt, xct, hyper["pull"], hyper["push"], "average", r_post_out=r)
+        elif args.call == "adamw_step":
+            state["t"] += 1
+            plan.local_adamw_step(xt, vt, m2t, gt, 5e-4, 0.9, 0.999, 1e-8, 0.01, state["t"])
         else:
             plan.local_sgd_step(xt, vt, gt, hyper["lr"], hyper["mu"], hyper["wd"])
 
@@ -155,11 +181,11 @@ def main() -> int:
         per_kernel.setdefault(name, []).append(ms)
     avg_ms = {k: sum(vv) / len(vv) for k, vv in per_kernel.items()}
     dominant = max(avg_ms, key=lambda k: avg_ms[k])
-    achieved = BYTES_PER_RP[dominant] * n_rp / (avg_ms[dominant] * 1e-3) / 1e9
+    achieved = bytes_per_rp[dominant] * n_rp / (avg_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(dominant, spec.name),
                 "avg_kernel_ms": avg_ms[dominant],
-                "algorithmic_bytes_per_launch": BYTES_PER_RP[dominant] * n_rp}
+                "algorithmic_bytes_per_launch": bytes_per_rp[dominant] * n_rp}
     torch.cuda.synchronize()
     assert torch.isfinite(r).all() and torch.isfinite(x[0][-1]).all()
 
@@ -179,8 +205,8 @@ def main() -> int:
         "config": {"workload": spec.name, "call": f"dppf_{args.call}", "M": spec.M, "d": spec.d, "T": spec.T,
                    "replica_params": n_rp, "pull": hyper["pull"], "push": hyper["push"], "lr": hyper["lr"],
                    "momentum": hyper["mu"], "weight_decay": hyper["wd"]},
-        "effective_GBps": CALL_BYTES[args.call] * value / 1e9,
-        "effective_frac_of_hbm_peak": CALL_BYTES[args.call] * value / 1e9 / HBM_PEAK_GBS,
+        "effective_GBps": call_bytes[args.call] * value / 1e9,
+        "effective_frac_of_hbm_peak": call_bytes[args.call] * value / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": avg_ms,
         "roofline": roofline,
     }
