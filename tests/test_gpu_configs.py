@@ -108,3 +108,34 @@ def test_config(name, fused):
     avg = before.mean(axis=0)
     assert np.all(np.sum(step * (before - avg), axis=1) > 0), "push-only step does not point away from the average"
     plan.close()
+
+
+def test_single_tensor_beyond_two_gib():
+    # one tensor of 2^29 + 5 floats per worker: byte offsets inside a tensor pass 2^31, the tile
+    # list has 131,073 entries and a ragged tail
+    d = (1 << 29) + 5
+    spec = W.WorkloadSpec("flat_2gib_M2", 2, ((d,),), seed=11, tau=1)
+    print(f"\n[{spec.name}] d={d}", flush=True)
+    lr, mu, wd, pull, push = f32(spec.lr), f32(spec.momentum), 0.0, f32(spec.pull), f32(spec.push)
+    inp = W.make_inputs(spec)
+    g_host = inp.grads(0)
+    x = [upload_tensors(a, inp.offsets) for a in inp.x]
+    v = [upload_tensors(a, inp.offsets) for a in inp.v]
+    g = [upload_tensors(a, inp.offsets) for a in g_host]
+    r = torch.zeros(2, device="cuda")
+    c = torch.zeros(2, device="cuda")
+    plan = dppf.Plan(2, spec.numel)
+    plan.round(x, v, g, lr, mu, wd, pull, push, r_out=r, c_out=c)
+    torch.cuda.synchronize()
+    x_pre, v_ref = oracle_local_steps(np.stack(inp.x), np.stack(inp.v), lambda _k: g_host, 1, lr, mu, wd)
+    del g_host
+    ref_x, ref_r, ref_c, _ = O.pull_push_round(x_pre, pull, push)
+    print(f"  r gpu {r.cpu().numpy()} oracle {ref_r}", flush=True)
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+    assert_rel(c.cpu().numpy(), ref_c, 1e-4, "c")
+    got = download_rows(x)
+    assert_params_close(got, ref_x, inp.offsets, 1, "x")
+    assert_update_close(got, ref_x, x_pre, "round")
+    del got, ref_x, x_pre
+    assert_params_close(download_rows(v), v_ref, inp.offsets, 1, "v")
+    plan.close()

@@ -334,3 +334,40 @@ def test_non_default_stream_and_timing_records():
     assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
     assert plan.timing_read() == []
     plan.close()
+
+
+def test_round_captured_in_a_hip_graph_replays_like_eager_calls():
+    # the entry points only enqueue, so a fused round can be captured once and replayed; every
+    # replay (with eager work and synchronisation in between) must equal the eager call bit for bit
+    spec = W.small_spec(M=4, seed=59, shapes=((50_000,), (333,), (70_001,)))
+    h = _hyper(spec)
+    inp = W.make_inputs(spec)
+    gk = inp.grads(0)
+    plan_a, plan_b = dppf.Plan(4, spec.numel), dppf.Plan(4, spec.numel)
+    xa, va, ga = _dev_rows(inp, inp.x), _dev_rows(inp, inp.v), _dev_rows(inp, gk)
+    xb, vb, gb = _dev_rows(inp, inp.x), _dev_rows(inp, inp.v), _dev_rows(inp, gk)
+    ra = torch.zeros(4, device="cuda")
+    rb = torch.zeros(4, device="cuda")
+    ta = [dppf.PointerTable(t) for t in (xa, va, ga)]
+    tb = [dppf.PointerTable(t) for t in (xb, vb, gb)]
+    args = (h["lr"], h["mu"], h["wd"], h["pull"], h["push"])
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):                 # first call uploads the pointer tables
+        plan_a.round(*ta, *args, r_out=ra)
+    side.synchronize()
+    plan_b.round(*tb, *args, r_out=rb)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        plan_a.round(*ta, *args, r_out=ra)
+    for k in range(4):
+        graph.replay()
+        plan_b.round(*tb, *args, r_out=rb)        # eager twin
+        torch.cuda.synchronize()
+        scratch = torch.randn(1 << 16, device="cuda").sum().item()   # unrelated eager work between replays
+        assert np.isfinite(scratch)
+        assert np.array_equal(download_rows(xa), download_rows(xb)), f"replay {k}: x differs"
+        assert np.array_equal(download_rows(va), download_rows(vb)), f"replay {k}: v differs"
+        assert np.array_equal(ra.cpu().numpy(), rb.cpu().numpy()), f"replay {k}: r differs"
+    plan_a.close()
+    plan_b.close()
