@@ -37,7 +37,8 @@ BYTES_PER_RP = {
     "adamw_step": 28.0,         # read x, m1, m2, g; write x, m1, m2
 }
 CALL_BYTES = {"round": 28.0, "pull_push": 12.0, "local_step": 20.0, "pull_push_exact": 12.0,
-              "pull_then_push": None, "adamw_step": 28.0}       # None: depends on M, see below
+              "pull_then_push": None, "adamw_step": 28.0,       # None: depends on M or tau, see below
+              "schedule": None}
 
 
 def kernel_source_hash() -> str:
@@ -120,6 +121,7 @@ def main() -> int:
     bytes_per_rp["seq_update"] = 8.0 + 4.0 / spec.M
     call_bytes = dict(CALL_BYTES)
     call_bytes["pull_then_push"] = 12.0 + 8.0 / spec.M
+    call_bytes["schedule"] = 20.0 * (spec.tau - 1) + 28.0     # tau-1 stand-alone steps + the fused round
     if args.call == "adamw_step":
         m2 = rows(inp.v)
     if args.call == "pull_then_push":
@@ -135,6 +137,11 @@ def main() -> int:
 
     def step():
         if args.call == "round":
+            plan.round(xt, vt, gt, hyper["lr"], hyper["mu"], hyper["wd"], hyper["pull"], hyper["push"], r_out=r,
+                       c_out=c)
+        elif args.call == "schedule":                        # the configuration's whole period
+            for _ in range(spec.tau - 1):
+                plan.local_sgd_step(xt, vt, gt, hyper["lr"], hyper["mu"], hyper["wd"])
             plan.round(xt, vt, gt, hyper["lr"], hyper["mu"], hyper["wd"], hyper["pull"], hyper["push"], r_out=r,
                        c_out=c)
         elif args.call == "pull_push":
@@ -174,13 +181,13 @@ def main() -> int:
     plan.timing_enable(True)
     for _ in range(args.steps):
         step()
-    recs = plan.timing_read(cap=8 * args.steps + 8)
+    recs = plan.timing_read(cap=(8 + spec.tau) * args.steps + 8)
     plan.timing_enable(False)
     per_kernel = {}
     for name, ms in recs:
         per_kernel.setdefault(name, []).append(ms)
     avg_ms = {k: sum(vv) / len(vv) for k, vv in per_kernel.items()}
-    dominant = max(avg_ms, key=lambda k: avg_ms[k])
+    dominant = max(avg_ms, key=lambda k: avg_ms[k] * len(per_kernel[k]))     # most GPU time in total
     achieved = bytes_per_rp[dominant] * n_rp / (avg_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(dominant, spec.name),

@@ -796,6 +796,48 @@ __global__ __launch_bounds__(kBlock) void k_copy(float* __restrict__ dst, const 
   if (blockIdx.x == 0 && threadIdx.x < n - 4 * nvec) dst[4 * nvec + threadIdx.x] = src[4 * nvec + threadIdx.x];
 }
 
+// ------------------------------------ streaming probe: R read streams, W write streams
+// Stream k is the n floats at base + k*stride.  Each element's R values are added and the sum
+// (times w+1) is stored to W streams: streams R..R+W-1, or, with INPLACE, streams 0..W-1 (read
+// and written by the same lane).  Gives the device's practical bandwidth for a given read/write
+// mix, the ceiling the DPPF kernels are compared with.
+template <int R, int W, int U, bool INPLACE>
+__global__ __launch_bounds__(kBlock) void k_probe(float* __restrict__ base, long long stride, long long n,
+                                                  float* __restrict__ sink) {
+  const long long tile = static_cast<long long>(kBlock) * U * 4;
+  const long long ntiles = n / tile;
+  f4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (long long t = blockIdx.x; t < ntiles; t += gridDim.x) {
+    f4 v[U];
+#pragma unroll
+    for (int k = 0; k < U; ++k) v[k] = (f4){1.f, 2.f, 3.f, static_cast<float>(t)};
+    if (R > 0) {
+      f4 tmp[R > 0 ? R : 1][U];
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int k = 0; k < U; ++k)
+          tmp[r][k] = load4_stream<true>(base + r * stride + t * tile + 4 * (k * kBlock + threadIdx.x), 4);
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int k = 0; k < U; ++k) v[k] += tmp[r][k];
+    }
+    if (W > 0) {
+#pragma unroll
+      for (int w = 0; w < W; ++w)
+#pragma unroll
+        for (int k = 0; k < U; ++k)
+          store4_stream<true>(base + (INPLACE ? w : R + w) * stride + t * tile + 4 * (k * kBlock + threadIdx.x),
+                              v[k] * static_cast<float>(w + 1), 4);
+    } else {
+#pragma unroll
+      for (int k = 0; k < U; ++k) acc += v[k];
+    }
+  }
+  if (W == 0 && acc.x + acc.y + acc.z + acc.w == 123.456f) sink[0] = acc.x;   // keeps the loads alive
+}
+
 // =========================================================================== host side
 thread_local int g_last_hip_error = 0;
 
@@ -1514,6 +1556,42 @@ int dppf_util_copy(float* dst, const float* src, int64_t n, void* stream) {
                      static_cast<hipStream_t>(stream), dst, src, static_cast<long long>(n));
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
+}
+
+// ---- streaming probe (measurement aid)
+int dppf_util_stream_probe(float* base, int64_t stride, int64_t n, int reads, int writes, int inplace,
+                           int blocks_per_cu, void* stream) {
+  if (!base || n < 0 || stride < n || blocks_per_cu < 1 || blocks_per_cu > 16) return DPPF_EINVAL;
+  if (reinterpret_cast<uintptr_t>(base) & 15u || (stride & 3)) return DPPF_EINVAL;
+  int dev = 0, cus = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  const dim3 grid(static_cast<unsigned>(cus * blocks_per_cu)), block(kBlock);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  float* sink = base;   // never written unless a sum hits one magic value
+#define DPPF_PROBE(R_, W_, U_, IP_)                                                              \
+  if (reads == R_ && writes == W_ && (inplace != 0) == IP_) {                                    \
+    hipLaunchKernelGGL((k_probe<R_, W_, U_, IP_>), grid, block, 0, s, base, static_cast<long long>(stride), \
+                       static_cast<long long>(n), sink);                                         \
+    HIP_TRY(hipGetLastError());                                                                  \
+    return DPPF_OK;                                                                              \
+  }
+  DPPF_PROBE(1, 0, 4, false)
+  DPPF_PROBE(4, 0, 4, false)
+  DPPF_PROBE(12, 0, 1, false)
+  DPPF_PROBE(0, 1, 4, false)
+  DPPF_PROBE(0, 4, 4, false)
+  DPPF_PROBE(1, 1, 4, false)
+  DPPF_PROBE(4, 4, 2, false)
+  DPPF_PROBE(4, 4, 2, true)
+  DPPF_PROBE(8, 4, 1, false)
+  DPPF_PROBE(8, 4, 1, true)
+  DPPF_PROBE(12, 4, 1, false)
+  DPPF_PROBE(12, 4, 1, true)
+  DPPF_PROBE(12, 8, 1, false)
+  DPPF_PROBE(12, 8, 1, true)
+#undef DPPF_PROBE
+  return DPPF_EINVAL;   // this read/write mix is not instantiated
 }
 
 // ---- timing
