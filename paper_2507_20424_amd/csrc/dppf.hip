@@ -24,6 +24,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "dppf.h"
@@ -104,27 +105,31 @@ __device__ __forceinline__ float sumsq4(f4 d, float acc) {
   return acc;
 }
 
-// Average of M values written as x_0 + (sum_j (x_j - x_0)) / M: for identical replicas every
-// difference is exactly zero, so the average equals x_0 bit for bit for ANY M, and each
-// worker's gap is then exactly zero.  A power-of-two M multiplies by the exact reciprocal;
-// any other M divides (correctly rounded), so an average that is representable is hit exactly.
-__device__ __forceinline__ f4 mean_from_offsets(f4 s, f4 x0, int m_total, float inv_m) {
-  if ((m_total & (m_total - 1)) == 0) return fma4(s, inv_m, x0);
+// The average is handled in coordinates relative to worker 0:  mu = (sum_j (x_j - x_0)) / M is
+// the average minus x_0, and worker m's gap to the average is  x_A - x_m = mu - (x_m - x_0).
+// The differences x_j - x_0 of nearby replicas are exact or nearly so, so the gap keeps its full
+// relative precision instead of inheriting the rounding of x_A (an ulp of x, which the
+// coefficient alpha - lambda/r multiplies -- by hundreds for a strong push).  For identical
+// replicas every difference is exactly zero, so every gap is exactly zero for ANY M.  A
+// power-of-two M multiplies by the exact reciprocal; any other M divides (correctly rounded), so
+// a worker that sits exactly on a representable average gets an exactly zero gap as well.
+__device__ __forceinline__ f4 scale_by_inverse_count(f4 s, int m_total, float inv_m) {
+  if ((m_total & (m_total - 1)) == 0) return s * inv_m;
   const float mf = static_cast<float>(m_total);
   f4 q;
   q.x = s.x / mf;
   q.y = s.y / mf;
   q.z = s.z / mf;
   q.w = s.w / mf;
-  return q + x0;
+  return q;
 }
 
 template <int M>
-__device__ __forceinline__ f4 mean_of(const f4 (&x)[M], float inv_m) {
+__device__ __forceinline__ f4 mean_offset(const f4 (&x)[M], float inv_m) {
   f4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int m = 1; m < M; ++m) s += x[m] - x[0];
-  return mean_from_offsets(s, x[0], M, inv_m);
+  return scale_by_inverse_count(s, M, inv_m);
 }
 
 __device__ __forceinline__ double wave_sum(double v) {
@@ -245,16 +250,19 @@ __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* 
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-      f4 xbar;
       if (XBAR == 2) {
-        xbar = load4<FULL>(xb + e[k], n[k]);
-      } else {
-        xbar = mean_of<M>(xv[k], inv_m);
-        if (XBAR == 1) store4_stream<FULL>(xb + e[k], xbar, n[k]);
-      }
-      if (NORMS) {
+        const f4 xbar = load4<FULL>(xb + e[k], n[k]);
+        if (NORMS) {
 #pragma unroll
-        for (int m = 0; m < M; ++m) part[m] = sumsq4(xv[k][m] - xbar, part[m]);
+          for (int m = 0; m < M; ++m) part[m] = sumsq4(xv[k][m] - xbar, part[m]);
+        }
+      } else {
+        const f4 mu = mean_offset<M>(xv[k], inv_m);
+        if (XBAR == 1) store4_stream<FULL>(xb + e[k], xv[k][0] + mu, n[k]);
+        if (NORMS) {
+#pragma unroll
+          for (int m = 0; m < M; ++m) part[m] = sumsq4((xv[k][m] - xv[k][0]) - mu, part[m]);
+        }
       }
     }
   }
@@ -413,10 +421,13 @@ __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* 
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-      const f4 xbar = (XBAR == 2) ? load4_stream<FULL>(xb + e[k], n[k]) : mean_of<M>(xv[k], inv_m);
+      // ref - (x_m - base) is the gap x_A - x_m: base = 0, ref = x_A when the average is given,
+      // base = x_0, ref = mu otherwise
+      const f4 ref = (XBAR == 2) ? load4_stream<FULL>(xb + e[k], n[k]) : mean_offset<M>(xv[k], inv_m);
+      const f4 base = (XBAR == 2) ? (f4){0.f, 0.f, 0.f, 0.f} : xv[k][0];
 #pragma unroll
       for (int m = 0; m < M; ++m) {
-        const f4 moved = fma4(xbar - xv[k][m], c[m], xv[k][m]);
+        const f4 moved = fma4(ref - (xv[k][m] - base), c[m], xv[k][m]);
         store4_stream<FULL>(x[m] + e[k], skip[m] ? xv[k][m] : moved, n[k]);
       }
     }
@@ -487,13 +498,13 @@ __device__ __forceinline__ void exact_tile(const Tile tl, int T, float* const* _
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-      const f4 xbar = mean_of<M>(xv[k], inv_m);
+      const f4 mu = mean_offset<M>(xv[k], inv_m);
       f4 usum = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int m = 0; m < M; ++m) usum = fma4(xbar - xv[k][m], inv_r[m], usum);
+      for (int m = 0; m < M; ++m) usum = fma4(mu - (xv[k][m] - xv[k][0]), inv_r[m], usum);
 #pragma unroll
       for (int m = 0; m < M; ++m) {
-        f4 moved = fma4(xbar - xv[k][m], c[m], xv[k][m]);
+        f4 moved = fma4(mu - (xv[k][m] - xv[k][0]), c[m], xv[k][m]);
         moved = fma4(usum, k2, moved);
         store4_stream<FULL>(x[m] + e[k], moved, n[k]);
       }
@@ -551,7 +562,7 @@ __device__ __forceinline__ void seq_tile(const Tile tl, int T, float* const* __r
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-      const f4 ref = (REF == 0) ? mean_of<M>(xv[k], inv_m) : cv[k];
+      const f4 ref = (REF == 0) ? xv[k][0] + mean_offset<M>(xv[k], inv_m) : cv[k];
 #pragma unroll
       for (int m = 0; m < M; ++m) {
         const f4 pulled = fma4(cv[k], pull, xv[k][m] * keep);   // (1-alpha) x + alpha x_C: exactly x_C at alpha = 1
@@ -768,7 +779,7 @@ __device__ __forceinline__ void mean_any_tile(const Tile tl, int M, int T,
     const f4 x0 = load4<FULL>(xp[tl.tensor] + tl.offset + e, n);
     f4 s = {0.f, 0.f, 0.f, 0.f};
     for (int m = 1; m < M; ++m) s += load4<FULL>(xp[static_cast<size_t>(m) * T + tl.tensor] + tl.offset + e, n) - x0;
-    store4<FULL>(xb + e, mean_from_offsets(s, x0, M, inv_m), n);
+    store4<FULL>(xb + e, x0 + scale_by_inverse_count(s, M, inv_m), n);
   }
 }
 
@@ -883,6 +894,8 @@ struct dppf_plan {
   std::vector<long long> tensor_offset;     // start of tensor t inside xbar_scratch
   enum Role { RX = 0, RV, RG, RM1, RM2, RXBAR, RXBAR_SCRATCH, RXC, NROLES };
   PtrTable tab[NROLES];
+  // resident blocks per CU of each kernel that has been launched (queried once)
+  std::vector<std::pair<const void*, int>> occupancy;
   // timing
   bool timing = false;
   std::vector<TimingRec> recs;
@@ -960,10 +973,16 @@ int timing_end(dppf_plan* p, hipStream_t s) {
 
 // ---- grid sizes: enough resident blocks to fill every CU, never more blocks than tiles
 template <typename K>
-int grid_for(const dppf_plan* p, K kernel, int per_tile_items, int want_per_cu, int* gfull_out,
-             int* grid_out) {
+int grid_for(dppf_plan* p, K kernel, int per_tile_items, int want_per_cu, int* gfull_out, int* grid_out) {
   int per_cu = 0;
-  HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBlock, 0));
+  const void* key = reinterpret_cast<const void*>(kernel);
+  for (const auto& kv : p->occupancy)
+    if (kv.first == key) per_cu = kv.second;
+  if (per_cu == 0) {
+    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBlock, 0));
+    if (per_cu < 1) per_cu = 1;
+    p->occupancy.emplace_back(key, per_cu);
+  }
   if (per_cu < 1) per_cu = 1;
   if (per_cu > want_per_cu) per_cu = want_per_cu;
   if (per_cu > kMaxBlocksPerCU - 1) per_cu = kMaxBlocksPerCU - 1;
@@ -1209,6 +1228,12 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
 }  // namespace
 
 // =============================================================================== C ABI
+// No C++ exception may cross the boundary: entry points that can allocate on the host are
+// function-try-blocks ending in this.
+#define DPPF_CATCH                                        \
+  catch (const std::bad_alloc&) { return DPPF_ENOMEM; }   \
+  catch (...) { return DPPF_EINVAL; }
+
 extern "C" {
 
 const char* dppf_strerror(int code) {
@@ -1323,7 +1348,7 @@ int dppf_plan_create(dppf_plan** out, int M, int T, const int64_t* numel) {
 
 int64_t dppf_plan_dim(const dppf_plan* p) { return p ? p->d : 0; }
 
-int dppf_replica_mean(dppf_plan* p, const float* const* x, float* const* xbar, void* stream) {
+int dppf_replica_mean(dppf_plan* p, const float* const* x, float* const* xbar, void* stream) try {
   if (!p || !x || !xbar) return DPPF_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const void **xd = nullptr, **xbd = nullptr;
@@ -1342,10 +1367,10 @@ int dppf_replica_mean(dppf_plan* p, const float* const* x, float* const* xbar, v
     rc = launch_mean_any(p, xd, xbd, s);
   if (rc) return rc;
   return timing_end(p, s);
-}
+} DPPF_CATCH
 
 int dppf_dist_norms(dppf_plan* p, const float* const* x, const float* const* xbar, float* r_out,
-                    void* stream) {
+                    void* stream) try {
   if (!p || !x || !r_out) return DPPF_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const void **xd = nullptr, **xbd = nullptr;
@@ -1378,16 +1403,16 @@ int dppf_dist_norms(dppf_plan* p, const float* const* x, const float* const* xba
     if ((rc = timing_end(p, s))) return rc;
   }
   return launch_finalize(p, shape.grid, 0.f, 0.f, false, r_out, nullptr, s);
-}
+} DPPF_CATCH
 
 int dppf_pull_push_round(dppf_plan* p, float* const* x, float pull, float push, float* r_out,
-                         float* c_out, float* const* xbar_out, void* stream) {
+                         float* c_out, float* const* xbar_out, void* stream) try {
   return round_impl(p, false, x, nullptr, nullptr, 0.f, 0.f, 0.f, pull, push, r_out, c_out, xbar_out,
                     static_cast<hipStream_t>(stream));
-}
+} DPPF_CATCH
 
 int dppf_local_sgd_step(dppf_plan* p, float* const* x, float* const* v, const float* const* g, float lr,
-                        float momentum, float weight_decay, void* stream) {
+                        float momentum, float weight_decay, void* stream) try {
   if (!p || !x || !v || !g) return DPPF_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t n = static_cast<size_t>(p->M) * p->T;
@@ -1398,17 +1423,17 @@ int dppf_local_sgd_step(dppf_plan* p, float* const* x, float* const* v, const fl
   if ((rc = table_upload(p, dppf_plan::RG, reinterpret_cast<const void* const*>(g), n, s, &gd))) return rc;
   if (p->ntiles == 0) return DPPF_OK;
   return launch_local_step(p, xd, vd, gd, lr, momentum, weight_decay, s);
-}
+} DPPF_CATCH
 
 int dppf_round(dppf_plan* p, float* const* x, float* const* v, const float* const* g, float lr,
                float momentum, float weight_decay, float pull, float push, float* r_out, float* c_out,
-               float* const* xbar_out, void* stream) {
+               float* const* xbar_out, void* stream) try {
   return round_impl(p, true, x, v, g, lr, momentum, weight_decay, pull, push, r_out, c_out, xbar_out,
                     static_cast<hipStream_t>(stream));
-}
+} DPPF_CATCH
 
 int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float push_r, float* r_out,
-                               float* c_out, void* stream) {
+                               float* c_out, void* stream) try {
   if (!p || !x) return DPPF_EINVAL;
   if (p->M > kMaxTemplM) return DPPF_ELIMIT;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1425,10 +1450,10 @@ int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float 
   if ((rc = timing_begin(p, DPPF_K_UPDATE_EXACT, s))) return rc;
   if ((rc = launch_update_exact(p, xd, shape.grid, pull, push_r, r_out, c_out, s))) return rc;
   return timing_end(p, s);
-}
+} DPPF_CATCH
 
 int dppf_pull_then_push(dppf_plan* p, float* const* x, const float* const* x_c, float pull, float push,
-                        int push_from, float* r_post_out, void* stream) {
+                        int push_from, float* r_post_out, void* stream) try {
   if (!p || !x || !x_c || (push_from != DPPF_PUSH_FROM_AVERAGE && push_from != DPPF_PUSH_FROM_CONSENSUS))
     return DPPF_EINVAL;
   if (p->M > kMaxTemplM) return DPPF_ELIMIT;
@@ -1444,11 +1469,11 @@ int dppf_pull_then_push(dppf_plan* p, float* const* x, const float* const* x_c, 
   if (p->ntiles == 0) return launch_finalize(p, 0, 0.f, 0.f, false, r_post_out, nullptr, s);
   return push_from == DPPF_PUSH_FROM_AVERAGE ? launch_seq<0>(p, xd, xcd, pull, push, r_post_out, s)
                                              : launch_seq<1>(p, xd, xcd, pull, push, r_post_out, s);
-}
+} DPPF_CATCH
 
 int dppf_local_adamw_step(dppf_plan* p, float* const* x, float* const* m1, float* const* m2,
                           const float* const* g, float lr, float beta1, float beta2, float eps,
-                          float weight_decay, int64_t step, void* stream) {
+                          float weight_decay, int64_t step, void* stream) try {
   if (!p || !x || !m1 || !m2 || !g || step < 1) return DPPF_EINVAL;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t n = static_cast<size_t>(p->M) * p->T;
@@ -1471,7 +1496,7 @@ int dppf_local_adamw_step(dppf_plan* p, float* const* x, float* const* m1, float
                      beta1, beta2, eps, weight_decay, static_cast<float>(1.0 / bc1), static_cast<float>(1.0 / bc2));
   HIP_TRY(hipGetLastError());
   return timing_end(p, s);
-}
+} DPPF_CATCH
 
 int dppf_round_statistics(const float* r, int M, float pull, float push, float* out, void* stream) {
   if (!r || !out || M < 1 || M > DPPF_MAX_WORKERS) return DPPF_EINVAL;
@@ -1497,17 +1522,17 @@ static int flat_check(const dppf_plan* p, const void* base, int64_t ld) {
 }
 
 int dppf_pull_push_round_flat(dppf_plan* p, float* x, int64_t ld, float pull, float push, float* r_out,
-                              float* c_out, float* xbar_out, void* stream) {
+                              float* c_out, float* xbar_out, void* stream) try {
   int rc = flat_check(p, x, ld);
   if (rc) return rc;
   std::vector<float*> xt(static_cast<size_t>(p->M));
   for (int m = 0; m < p->M; ++m) xt[m] = x + static_cast<long long>(m) * ld;
   float* xb[1] = {xbar_out};
   return dppf_pull_push_round(p, xt.data(), pull, push, r_out, c_out, xbar_out ? xb : nullptr, stream);
-}
+} DPPF_CATCH
 
 int dppf_local_sgd_step_flat(dppf_plan* p, float* x, float* v, const float* g, int64_t ld, float lr,
-                             float momentum, float weight_decay, void* stream) {
+                             float momentum, float weight_decay, void* stream) try {
   int rc = flat_check(p, x, ld);
   if (rc) return rc;
   if (!v || !g) return DPPF_EINVAL;
@@ -1519,11 +1544,11 @@ int dppf_local_sgd_step_flat(dppf_plan* p, float* x, float* v, const float* g, i
     gt[m] = g + static_cast<long long>(m) * ld;
   }
   return dppf_local_sgd_step(p, xt.data(), vt.data(), gt.data(), lr, momentum, weight_decay, stream);
-}
+} DPPF_CATCH
 
 int dppf_round_flat(dppf_plan* p, float* x, float* v, const float* g, int64_t ld, float lr, float momentum,
                     float weight_decay, float pull, float push, float* r_out, float* c_out, float* xbar_out,
-                    void* stream) {
+                    void* stream) try {
   int rc = flat_check(p, x, ld);
   if (rc) return rc;
   if (!v || !g) return DPPF_EINVAL;
@@ -1537,7 +1562,7 @@ int dppf_round_flat(dppf_plan* p, float* x, float* v, const float* g, int64_t ld
   float* xb[1] = {xbar_out};
   return dppf_round(p, xt.data(), vt.data(), gt.data(), lr, momentum, weight_decay, pull, push, r_out,
                     c_out, xbar_out ? xb : nullptr, stream);
-}
+} DPPF_CATCH
 
 // ---- plain device-to-device copy of n floats with the library's own load/store path
 int dppf_util_copy(float* dst, const float* src, int64_t n, void* stream) {
@@ -1601,7 +1626,7 @@ int dppf_plan_timing_enable(dppf_plan* p, int enable) {
   return DPPF_OK;
 }
 
-int dppf_plan_timing_read(dppf_plan* p, int* kernel_id, float* ms, int cap) {
+int dppf_plan_timing_read(dppf_plan* p, int* kernel_id, float* ms, int cap) try {
   if (!p || cap < 0 || (cap > 0 && (!kernel_id || !ms))) return DPPF_EINVAL;
   int n = 0;
   for (auto& r : p->recs) {
@@ -1618,6 +1643,6 @@ int dppf_plan_timing_read(dppf_plan* p, int* kernel_id, float* ms, int cap) {
   }
   p->recs.clear();
   return n;
-}
+} DPPF_CATCH
 
 }  // extern "C"

@@ -2,12 +2,17 @@
 over the same host arrays, and the comparison rules.
 
 Tolerances (fp32 kernels against the float64 oracle):
-  parameters   |gpu - oracle| <= 1e-5 |oracle| + (4 + 2 tau) 2^-24 max|tensor|
+  parameters   |gpu - oracle| <= 1e-5 |oracle| + (4 + 2 tau) (1 + 2|c_m|) 2^-24 max|tensor|
                The relative term is the stated bar.  The absolute term covers elements that
                end up near zero by cancellation: each local step rounds x and v once
                (<= 1 ulp of the operands per step, tau steps), the round adds the rounding of
                the average, of the gap and of the final fused multiply-add (<= 4 ulp of the
-               operands).  It is about 1e-6 of the tensor's largest element.
+               operands).  The round computes x + (x_A - x) c from fp32 values of x, so whatever
+               rounding x already carries is multiplied by |1 - c| and that of x_A by |c|: the
+               factor (1 + 2|c_m|), which is 1.2 at the benchmark's hyper-parameters and matters
+               only for a strong push (|c| of 30..600 at the paper's ImageNet settings applied to
+               tightly clustered synthetic workers).  At |c| <= 1 the term is about 1e-6 of the
+               tensor's largest element.
   r_m, c_m     relative 1e-4
   update       || (gpu x+ - x_pre) - (oracle x+ - x_pre) ||_2 <= 1e-3 || oracle x+ - x_pre ||_2
                so that a wrong or missing push cannot hide inside the parameter tolerance.
@@ -96,7 +101,8 @@ def per_element_scale(ref: np.ndarray, offsets: np.ndarray) -> np.ndarray:
     return np.repeat(scale_t, np.diff(offsets))
 
 
-def assert_params_close(gpu: np.ndarray, ref: np.ndarray, offsets: np.ndarray, tau: int, what: str):
+def assert_params_close(gpu: np.ndarray, ref: np.ndarray, offsets: np.ndarray, tau: int, what: str, c=None):
+    """c: the oracle's coefficients c_m of the round that produced `ref` (None: no round, or |c| <= 1)."""
     assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
     if ref.size == 0:
         return
@@ -104,7 +110,8 @@ def assert_params_close(gpu: np.ndarray, ref: np.ndarray, offsets: np.ndarray, t
     scale = per_element_scale(ref, offsets)
     for m in range(ref.shape[0]):
         err = np.abs(gpu[m].astype(np.float64) - ref[m])
-        tol = 1e-5 * np.abs(ref[m]) + (4 + 2 * tau) * EPS32 * scale
+        amp = 1.0 if c is None else max(1.0, 1.0 + 2.0 * abs(float(c[m])))
+        tol = 1e-5 * np.abs(ref[m]) + (4 + 2 * tau) * amp * EPS32 * scale
         bad = err > tol
         if bad.any():
             i = int(np.argmax(err - tol))

@@ -371,3 +371,30 @@ def test_round_captured_in_a_hip_graph_replays_like_eager_calls():
         assert np.array_equal(ra.cpu().numpy(), rb.cpu().numpy()), f"replay {k}: r differs"
     plan_a.close()
     plan_b.close()
+
+
+@pytest.mark.parametrize("pull,push,wd", [(0.1, 0.5, 1e-3), (0.1, 0.75, 1e-3), (0.1, 1.0, 1e-4), (0.5, 5.0, 1e-4),
+                                          (0.9, 9.0, 1e-4), (0.9, 90.0, 0.0), (1.0, 0.0, 1e-3), (0.05, 0.05, 0.0)])
+def test_fused_round_with_the_hyperparameters_the_paper_uses(pull, push, wd):
+    # (alpha, lambda) pairs and weight decays from the paper's experiment sections: alpha = 0.1 with
+    # lambda 0.5..1.0 (CIFAR), lambda/alpha = 10 (ImageNet CNNs), alpha = 0.9 with lambda = 90 (ViT),
+    # full consensus alpha = 1, lambda = 0 (LocalSGD)
+    spec = W.small_spec(M=4, seed=600, tau=1, pull=pull, push=push, weight_decay=wd)
+    h = _hyper(spec)
+    inp = W.make_inputs(spec)
+    gk = inp.grads(0)
+    x, v, g = _dev_rows(inp, inp.x), _dev_rows(inp, inp.v), _dev_rows(inp, gk)
+    r = torch.zeros(4, device="cuda")
+    c = torch.zeros(4, device="cuda")
+    plan = dppf.Plan(4, spec.numel)
+    plan.round(x, v, g, h["lr"], h["mu"], h["wd"], h["pull"], h["push"], r_out=r, c_out=c)
+    x_pre, _ = O.local_sgd_step(np.stack(inp.x), np.stack(inp.v), np.stack(gk), h["lr"], h["mu"], h["wd"])
+    ref_x, ref_v, ref_r, ref_c, _ = O.dppf_round(np.stack(inp.x), np.stack(inp.v), np.stack(gk), h["lr"], h["mu"],
+                                                 h["wd"], h["pull"], h["push"])
+    got = download_rows(x)
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+    assert_rel(c.cpu().numpy(), ref_c, 1e-4, "c")
+    assert_params_close(got, ref_x, inp.offsets, 1, "x", c=ref_c)
+    assert_params_close(download_rows(v), ref_v, inp.offsets, 1, "v")
+    assert_update_close(got, ref_x, x_pre, "round")
+    plan.close()
