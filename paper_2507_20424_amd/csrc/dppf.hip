@@ -39,10 +39,10 @@ constexpr int kTileElems = 4096;              // elements of ONE worker's tensor
 constexpr int kVecPerThread = kTileElems / (4 * kBlock);   // 16-byte vectors per thread per tile
 constexpr int kMaxTemplM = 8;                 // worker counts with a register-resident kernel
 constexpr int kMaxBlocksPerCU = 8;             // upper bound on resident blocks per CU (sizes buffers)
-// Resident blocks per CU by traffic pattern.  Kernels that only read want many loads in flight;
-// kernels that mix reads and writes run fastest with ONE block per CU: fewer concurrently open
-// DRAM rows and longer same-direction bursts outweigh the lost latency hiding.
-constexpr int kBlocksPerCUReadOnly = 8;
+// Resident blocks per CU by traffic pattern (measured): kernels that mix reads and writes run
+// fastest with ONE block per CU -- fewer concurrently open DRAM rows and longer same-direction
+// bursts outweigh the lost latency hiding; kernels that only read do best with two.
+constexpr int kBlocksPerCUReadOnly = 2;
 constexpr int kBlocksPerCUReadWrite = 1;
 constexpr bool kDeferStepStore = true;        // fused round: x after the local step is never stored
 
@@ -185,7 +185,8 @@ __device__ __forceinline__ TileWalk tile_walk(int nfull, int ntiles, int gfull) 
 // --------------------------------------------------------------------- sweep 1 of the round
 // XBAR: 0 = average stays in registers, 1 = also written out, 2 = read from memory instead of
 // being recomputed (dppf_dist_norms with a given x_A).
-template <int M, int U, bool SGD, int XBAR, bool NORMS, bool FULL>
+// KEEPX: load x through the caches (it is read again soon) instead of streaming it past them.
+template <int M, int U, bool SGD, int XBAR, bool NORMS, bool FULL, bool KEEPX>
 __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* __restrict__ xp,
                                             float* const* __restrict__ vp,
                                             const float* const* __restrict__ gp,
@@ -223,7 +224,7 @@ __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* 
       for (int k = 0; k < U; ++k)
 #pragma unroll
         for (int m = 0; m < M; ++m) {
-          xv[k][m] = load4<FULL>(x[m] + e[k], n[k]);
+          xv[k][m] = KEEPX ? load4<FULL>(x[m] + e[k], n[k]) : load4_stream<FULL>(x[m] + e[k], n[k]);
           vv[k][m] = load4_stream<FULL>(v[m] + e[k], n[k]);
           gv[k][m] = load4_stream<FULL>(g[m] + e[k], n[k]);
         }
@@ -246,7 +247,8 @@ __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* 
 #pragma unroll
       for (int k = 0; k < U; ++k)
 #pragma unroll
-        for (int m = 0; m < M; ++m) xv[k][m] = load4<FULL>(x[m] + e[k], n[k]);
+        for (int m = 0; m < M; ++m)
+          xv[k][m] = KEEPX ? load4<FULL>(x[m] + e[k], n[k]) : load4_stream<FULL>(x[m] + e[k], n[k]);
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) {
@@ -280,18 +282,24 @@ __global__ __launch_bounds__(kBlock) void k_sweep1(const Tile* __restrict__ tile
                                                    const float* const* __restrict__ gp,
                                                    float* const* __restrict__ xbarp, float lr,
                                                    float mu, float wd, double* __restrict__ partials,
-                                                   int pstride) {
+                                                   int pstride, int keep_from) {
   double acc[M];
 #pragma unroll
   for (int m = 0; m < M; ++m) acc[m] = 0.0;
   const float inv_m = 1.0f / static_cast<float>(M);
   const TileWalk w = tile_walk(nfull, ntiles, gfull);
   if (w.full) {
-    for (int t = w.first; t < w.end; t += w.stride)
-      sweep1_tile<M, U, SGD, XBAR, NORMS, true>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
+    // Pure reads stream fastest when they bypass the last-level cache, but the tiles this sweep
+    // touches last are the ones sweep 2 (which walks backwards) reads first: those, from
+    // keep_from on, go through the cache so that sweep 2 finds them there.
+    int t = w.first;
+    for (; t < w.end && t < keep_from; t += w.stride)
+      sweep1_tile<M, U, SGD, XBAR, NORMS, true, false>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
+    for (; t < w.end; t += w.stride)
+      sweep1_tile<M, U, SGD, XBAR, NORMS, true, true>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
   } else {
     for (int t = w.first; t < w.end; t += w.stride)
-      sweep1_tile<M, U, SGD, XBAR, NORMS, false>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
+      sweep1_tile<M, U, SGD, XBAR, NORMS, false, true>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
   }
   if (NORMS) block_sums_store<M>(acc, partials + static_cast<size_t>(blockIdx.x) * pstride);
 }
@@ -1003,6 +1011,22 @@ struct GridShape {
   int gfull = 0, grid = 0;
 };
 
+// Which of sweep 1's x loads go through the caches (see k_sweep1).
+enum KeepPolicy {
+  kKeepAll,      // every tile: sweep 2 follows and the loads are not the bottleneck (fused sweep 1)
+  kKeepTail,     // only the tiles touched last, as many as fit the last-level cache budget
+  kKeepNone      // nothing reads x again soon
+};
+constexpr long long kLastLevelCacheBudget = 256ll << 20;   // bytes of x worth keeping (the cache is 256 MB)
+
+int keep_from_tile(const dppf_plan* p, int workers, KeepPolicy keep) {
+  if (keep == kKeepAll) return 0;
+  if (keep == kKeepNone) return p->nfull;
+  const long long per_tile = static_cast<long long>(workers) * kTileElems * sizeof(float);
+  const long long tiles = kLastLevelCacheBudget / per_tile;
+  return tiles >= p->nfull ? 0 : p->nfull - static_cast<int>(tiles);
+}
+
 constexpr int unroll_plain(int M) { return M <= 4 ? 4 : (M <= 8 ? 2 : 1); }   // M*U <= 16 vectors
 constexpr int unroll_step_update(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }   // 2*M*U <= 16 vectors
 constexpr int unroll_fused(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }   // 3*M*U <= 24 vectors
@@ -1023,7 +1047,7 @@ constexpr int unroll_fused(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }   //
 // Launch sweep 1 over workers [m0, m0+mg) of the table (mg <= 8).
 template <bool SGD, int XBAR, bool NORMS>
 int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const void** gp,
-                  const void** xbarp, float lr, float mu, float wd, int m0, GridShape* shape,
+                  const void** xbarp, float lr, float mu, float wd, int m0, KeepPolicy keep, GridShape* shape,
                   hipStream_t s) {
   float* const* x = (float* const*)(xp) + static_cast<size_t>(m0) * p->T;
   float* const* v = vp ? (float* const*)(vp) + static_cast<size_t>(m0) * p->T : nullptr;
@@ -1046,7 +1070,7 @@ int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const 
       }
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, v, g, xb,
-                       lr, mu, wd, p->partials + m0, p->M);
+                       lr, mu, wd, p->partials + m0, p->M, keep_from_tile(p, mg, keep));
   })
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
@@ -1185,11 +1209,11 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
   if (p->M <= kMaxTemplM) {
     if ((rc = timing_begin(p, with_step ? DPPF_K_STEP_REDUCE : DPPF_K_REDUCE, s))) return rc;
     if (with_step) {
-      rc = xbar_out ? launch_sweep1<true, 1, true>(p, p->M, xd, vd, gd, xbd, lr, mu, wd, 0, &shape, s)
-                    : launch_sweep1<true, 0, true>(p, p->M, xd, vd, gd, nullptr, lr, mu, wd, 0, &shape, s);
+      rc = xbar_out ? launch_sweep1<true, 1, true>(p, p->M, xd, vd, gd, xbd, lr, mu, wd, 0, kKeepAll, &shape, s)
+                    : launch_sweep1<true, 0, true>(p, p->M, xd, vd, gd, nullptr, lr, mu, wd, 0, kKeepAll, &shape, s);
     } else {
-      rc = xbar_out ? launch_sweep1<false, 1, true>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, &shape, s)
-                    : launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, &shape, s);
+      rc = xbar_out ? launch_sweep1<false, 1, true>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, kKeepTail, &shape, s)
+                    : launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, kKeepTail, &shape, s);
     }
     if (rc) return rc;
     if ((rc = timing_end(p, s))) return rc;
@@ -1212,7 +1236,7 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
   if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
   for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
     const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
-    if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, &shape, s))) return rc;
+    if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, kKeepNone, &shape, s))) return rc;
   }
   if ((rc = timing_end(p, s))) return rc;
   if ((rc = launch_finalize(p, shape.grid, pull, push, true, r_out, c_out, s))) return rc;
@@ -1362,7 +1386,7 @@ int dppf_replica_mean(dppf_plan* p, const float* const* x, float* const* xbar, v
   if (p->ntiles == 0) return DPPF_OK;
   if ((rc = timing_begin(p, DPPF_K_MEAN, s))) return rc;
   if (p->M <= kMaxTemplM)
-    rc = launch_sweep1<false, 1, false>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, nullptr, s);
+    rc = launch_sweep1<false, 1, false>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, kKeepNone, nullptr, s);
   else
     rc = launch_mean_any(p, xd, xbd, s);
   if (rc) return rc;
@@ -1385,8 +1409,8 @@ int dppf_dist_norms(dppf_plan* p, const float* const* x, const float* const* xba
   GridShape shape;
   if (p->M <= kMaxTemplM) {
     if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
-    rc = xbar ? launch_sweep1<false, 2, true>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, &shape, s)
-              : launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, &shape, s);
+    rc = xbar ? launch_sweep1<false, 2, true>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, kKeepNone, &shape, s)
+              : launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, kKeepNone, &shape, s);
     if (rc) return rc;
     if ((rc = timing_end(p, s))) return rc;
   } else {
@@ -1398,7 +1422,7 @@ int dppf_dist_norms(dppf_plan* p, const float* const* x, const float* const* xba
     if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
     for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
       const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
-      if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, &shape, s))) return rc;
+      if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, kKeepNone, &shape, s))) return rc;
     }
     if ((rc = timing_end(p, s))) return rc;
   }
@@ -1445,7 +1469,7 @@ int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float 
   if (p->ntiles == 0) return launch_finalize(p, 0, pull, push_r / static_cast<float>(p->M), false, r_out, c_out, s);
   GridShape shape;
   if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
-  if ((rc = launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, &shape, s))) return rc;
+  if ((rc = launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, kKeepTail, &shape, s))) return rc;
   if ((rc = timing_end(p, s))) return rc;
   if ((rc = timing_begin(p, DPPF_K_UPDATE_EXACT, s))) return rc;
   if ((rc = launch_update_exact(p, xd, shape.grid, pull, push_r, r_out, c_out, s))) return rc;
