@@ -1,18 +1,25 @@
 // DPPF consensus round and local step for MI355X (gfx950, wave64).
 //
 // The work is bandwidth-bound streaming over the M workers' parameter tensors, so the design
-// is about bytes, not flops:
-//   * the round is two sweeps over x with a tiny finalize step between them, because the
-//     per-worker coefficient alpha - lambda/r_m (Sec. 5, Eq. 5) needs r_m, a reduction over
-//     the whole model: sweep 1 reads x once (average kept in registers, squared distances
-//     accumulated), sweep 2 reads x again, recomputes the average from the same M loads and
-//     writes x.  12 bytes per replica-parameter; the fused form folds the last local step
-//     (Alg. 1, SGD line) into sweep 1 for 28 bytes instead of 32.
-//   * a tensor list is cut into tiles of kTileElems consecutive elements of one tensor;
-//     thread blocks walk the tile list with a grid stride, so one launch covers any number
-//     of tensors of any size.  Loads are 16-byte vectors with 4-byte alignment (legal for
-//     global memory on gfx9), so no tensor needs 16-byte alignment; only the last, partial
-//     vector of a tensor is handled element by element.
+// is about bytes and about what the memory system likes, not about flops:
+//   * the round is two sweeps over x, because the per-worker coefficient alpha - lambda/r_m
+//     (Sec. 5, Eq. 5) needs r_m, a reduction over the whole model, before any element moves:
+//     sweep 1 reads x once (average kept in registers, squared distances accumulated into
+//     per-block partial sums), sweep 2 turns the partial sums into the coefficients, reads x
+//     again, recomputes the average from the same M loads and writes x.  12 bytes per
+//     replica-parameter.
+//   * the fused form folds the last local step (Alg. 1, SGD line) into sweep 1 and never stores
+//     the stepped x: sweep 1 reads x, v, g and writes only v; sweep 2 reads the OLD x and the NEW
+//     v, rebuilds x - lr v with the same fused multiply-add (same bits) and applies Eq. 5.
+//     28 bytes instead of 32, and 20 of them reads (reads stream faster than writes here).
+//   * a tensor list is cut into tiles of kTileElems consecutive elements of one tensor; thread
+//     blocks walk the tile list with a grid stride, so one launch covers any number of tensors
+//     of any size.  Full tiles and partial ones (tensor tails, small tensors) are walked by
+//     different blocks.  Loads are 16-byte vectors with 4-byte alignment (legal for global
+//     memory on gfx9), so no tensor needs 16-byte alignment; only the last, partial vector of a
+//     tensor is handled element by element.
+//   * the gap of a worker to the average is formed relative to worker 0 (see mean_offset), so it
+//     keeps full relative precision and is exactly zero for identical replicas.
 //   * squared distances: fp32 inside a tile (16 values per lane), fp64 across tiles, lanes,
 //     waves and blocks, in a fixed order -- results are bit-reproducible run to run.
 //   * sweep 2 walks the tiles in the opposite order to sweep 1, so that the part of x that
@@ -44,7 +51,6 @@ constexpr int kMaxBlocksPerCU = 8;             // upper bound on resident blocks
 // bursts outweigh the lost latency hiding; kernels that only read do best with two.
 constexpr int kBlocksPerCUReadOnly = 2;
 constexpr int kBlocksPerCUReadWrite = 1;
-constexpr bool kDeferStepStore = true;        // fused round: x after the local step is never stored
 
 struct Tile {
   long long offset;   // first element inside the tensor
@@ -237,10 +243,9 @@ __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* 
           f4 vn = fma4(vv[k][m], mu, ge);
           f4 xn = fma4(vn, -lr, xv[k][m]);
           store4_stream<FULL>(v[m] + e[k], vn, n[k]);
-          // With the deferred form the stepped x is not written here: sweep 2 re-derives it from
-          // the old x and the new v with the same fused multiply-add (same bits), which trades 4
-          // written bytes for 4 read bytes per element -- reads are the cheaper direction.
-          if (!kDeferStepStore) store4<FULL>(x[m] + e[k], xn, n[k]);
+          // The stepped x is not written: sweep 2 re-derives it from the old x and the new v with
+          // the same fused multiply-add (same bits), which trades 4 written bytes for 4 read bytes
+          // per element -- reads are the cheaper direction.
           xv[k][m] = xn;
         }
     } else {
@@ -931,6 +936,7 @@ int table_upload(dppf_plan* p, int role, const void* const* host, size_t n, hipS
     if ((reinterpret_cast<uintptr_t>(host[i]) & 3u) != 0) return DPPF_EINVAL;
   }
   HIP_TRY(hipEventSynchronize(t.uploaded));   // the previous upload has left the staging buffer
+  t.valid = false;                            // until the new contents are on their way
   std::memcpy(t.staging, host, n * sizeof(void*));
   HIP_TRY(hipMemcpyAsync(t.dev, t.staging, n * sizeof(void*), hipMemcpyHostToDevice, s));
   HIP_TRY(hipEventRecord(t.uploaded, s));
@@ -1217,8 +1223,8 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
     }
     if (rc) return rc;
     if ((rc = timing_end(p, s))) return rc;
-    if ((rc = timing_begin(p, (with_step && kDeferStepStore) ? DPPF_K_STEP_UPDATE : DPPF_K_UPDATE, s))) return rc;
-    if (with_step && kDeferStepStore)
+    if ((rc = timing_begin(p, with_step ? DPPF_K_STEP_UPDATE : DPPF_K_UPDATE, s))) return rc;
+    if (with_step)
       rc = launch_sweep2<0, true, true>(p, p->M, xd, vd, nullptr, lr, 0, shape.grid, pull, push, r_out, c_out, s);
     else
       rc = launch_sweep2<0, false, true>(p, p->M, xd, nullptr, nullptr, 0.f, 0, shape.grid, pull, push, r_out, c_out, s);
