@@ -35,10 +35,11 @@ BYTES_PER_RP = {
     "seq_reduce": None,         # read x and x_C: 4 + 4/M
     "seq_update": None,         # read x and x_C, write x: 8 + 4/M
     "adamw_step": 28.0,         # read x, m1, m2, g; write x, m1, m2
+    "adamw_reduce": 28.0,       # the same traffic, with the average and distances riding along
 }
 CALL_BYTES = {"round": 28.0, "pull_push": 12.0, "local_step": 20.0, "pull_push_exact": 12.0,
               "pull_then_push": None, "adamw_step": 28.0,       # None: depends on M or tau, see below
-              "schedule": None}
+              "schedule": None, "round_adamw": 36.0}
 
 
 def kernel_source_hash() -> str:
@@ -122,7 +123,7 @@ def main() -> int:
     call_bytes = dict(CALL_BYTES)
     call_bytes["pull_then_push"] = 12.0 + 8.0 / spec.M
     call_bytes["schedule"] = 20.0 * (spec.tau - 1) + 28.0     # tau-1 stand-alone steps + the fused round
-    if args.call == "adamw_step":
+    if args.call in ("adamw_step", "round_adamw"):
         m2 = rows(inp.v)
     if args.call == "pull_then_push":
         xc = [torch.from_numpy(inp.x[0][inp.offsets[t]:inp.offsets[t + 1]]).to("cuda") for t in range(spec.T)]
@@ -133,7 +134,7 @@ def main() -> int:
     xt, vt, gt = dppf.PointerTable(x), dppf.PointerTable(v), dppf.PointerTable(g)
 
     state = {"t": 0}
-    m2t = dppf.PointerTable(m2) if args.call == "adamw_step" else None
+    m2t = dppf.PointerTable(m2) if args.call in ("adamw_step", "round_adamw") else None
 
     def step():
         if args.call == "round":
@@ -153,6 +154,10 @@ def main() -> int:
         elif args.call == "adamw_step":
             state["t"] += 1
             plan.local_adamw_step(xt, vt, m2t, gt, 5e-4, 0.9, 0.999, 1e-8, 0.01, state["t"])
+        elif args.call == "round_adamw":
+            state["t"] += 1
+            plan.round_adamw(xt, vt, m2t, gt, 5e-4, 0.9, 0.999, 1e-8, 0.01, state["t"], hyper["pull"],
+                             hyper["push"], r_out=r, c_out=c)
         else:
             plan.local_sgd_step(xt, vt, gt, hyper["lr"], hyper["mu"], hyper["wd"])
 

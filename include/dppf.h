@@ -101,8 +101,10 @@ int dppf_local_sgd_step(dppf_plan* plan, float* const* x, float* const* v,
                         const float* const* g, float lr, float momentum, float weight_decay,
                         void* stream);
 
-/* Fused: exactly dppf_local_sgd_step followed by dppf_pull_push_round, but the step is
- * folded into the round's first sweep so x is read one time less.  */
+/* Fused: dppf_local_sgd_step followed by dppf_pull_push_round, with the step folded into the
+ * round's first sweep so x is read one time less.  Same arithmetic per element; the squared
+ * distances may be summed in a different order than in the two separate calls (the grids can
+ * differ), so r_m agrees to rounding and everything else follows from it.  */
 int dppf_round(dppf_plan* plan, float* const* x, float* const* v, const float* const* g,
                float lr, float momentum, float weight_decay, float pull, float push,
                float* r_out, float* c_out, float* const* xbar_out, void* stream);
@@ -139,6 +141,14 @@ int dppf_pull_then_push(dppf_plan* plan, float* const* x, const float* const* x_
 int dppf_local_adamw_step(dppf_plan* plan, float* const* x, float* const* m1, float* const* m2,
                           const float* const* g, float lr, float beta1, float beta2, float eps,
                           float weight_decay, int64_t step, void* stream);
+
+/* Fused: dppf_local_adamw_step followed by dppf_pull_push_round, with the step folded into the
+ * round's first sweep (x is read one time less: 36 instead of 40 bytes per replica-parameter;
+ * same remark on the summation order as for dppf_round).  r_out, c_out optional.  */
+int dppf_round_adamw(dppf_plan* plan, float* const* x, float* const* m1, float* const* m2,
+                     const float* const* g, float lr, float beta1, float beta2, float eps,
+                     float weight_decay, int64_t step, float pull, float push, float* r_out,
+                     float* c_out, void* stream);
 
 /* What the paper logs every round (appendix "Pull-Push Mechanism"), from the distances r (device,
  * M floats, e.g. r_out of a round):  out[0] = relaxed MV = (1/M) sum_m r_m;
@@ -181,7 +191,8 @@ enum {
   DPPF_K_UPDATE_EXACT = 7, /* sweep 2 with the two-term gradient                         */
   DPPF_K_SEQ_REDUCE = 8,   /* dppf_pull_then_push, sweep 1                               */
   DPPF_K_SEQ_UPDATE = 9,   /* dppf_pull_then_push, sweep 2                               */
-  DPPF_K_ADAMW_STEP = 10   /* AdamW local step                                           */
+  DPPF_K_ADAMW_STEP = 10,  /* AdamW local step                                           */
+  DPPF_K_ADAMW_REDUCE = 11 /* sweep 1 of the fused AdamW round                           */
 };
 int dppf_plan_timing_enable(dppf_plan* plan, int enable);
 int dppf_plan_timing_read(dppf_plan* plan, int* kernel_id, float* ms, int cap);

@@ -51,6 +51,9 @@ constexpr int kMaxBlocksPerCU = 8;             // upper bound on resident blocks
 // bursts outweigh the lost latency hiding; kernels that only read do best with two.
 constexpr int kBlocksPerCUReadOnly = 2;
 constexpr int kBlocksPerCUReadWrite = 1;
+// The fused AdamW sweep does a division and a square root per element between its loads and its
+// stores; one wave per SIMD cannot hide that, so it gets more resident blocks.
+constexpr int kBlocksPerCUHeavyMath = 3;
 
 struct Tile {
   long long offset;   // first element inside the tensor
@@ -644,10 +647,34 @@ __global__ __launch_bounds__(kBlock) void k_seq2(const Tile* __restrict__ tiles,
 // ------------------------------------------------------------------ AdamW local step
 // Decoupled weight decay Adam: x <- x (1 - lr wd); m <- b1 m + (1-b1) g; s <- b2 s + (1-b2) g^2;
 // x <- x - lr (m / bc1) / (sqrt(s / bc2) + eps), bc_i = 1 - b_i^t computed on the host.
+struct AdamHyper {
+  float lr, b1, b2, eps, wd, inv_bc1, inv_bc2;
+};
+
+__device__ __forceinline__ void adamw_vec(const f4& xv, const f4& av, const f4& sv, const f4& gv,
+                                          const AdamHyper& hp, f4& xn, f4& an, f4& sn) {
+  const float* xs = reinterpret_cast<const float*>(&xv);
+  const float* as = reinterpret_cast<const float*>(&av);
+  const float* ss = reinterpret_cast<const float*>(&sv);
+  const float* gs = reinterpret_cast<const float*>(&gv);
+  float* xo = reinterpret_cast<float*>(&xn);
+  float* ao = reinterpret_cast<float*>(&an);
+  float* so = reinterpret_cast<float*>(&sn);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float xd = __builtin_fmaf(-hp.lr * hp.wd, xs[i], xs[i]);
+    const float a = __builtin_fmaf(hp.b1, as[i], (1.0f - hp.b1) * gs[i]);
+    const float q = __builtin_fmaf(hp.b2, ss[i], (1.0f - hp.b2) * gs[i] * gs[i]);
+    const float denom = __builtin_sqrtf(q * hp.inv_bc2) + hp.eps;
+    xo[i] = xd - hp.lr * (a * hp.inv_bc1) / denom;
+    ao[i] = a;
+    so[i] = q;
+  }
+}
+
 template <int U, bool FULL>
-__device__ __forceinline__ void adamw_tile(float* x, float* m1, float* m2, const float* g, int count, float lr,
-                                           float b1, float b2, float eps, float wd, float inv_bc1,
-                                           float inv_bc2) {
+__device__ __forceinline__ void adamw_tile(float* x, float* m1, float* m2, const float* g, int count,
+                                           const AdamHyper hp) {
 #pragma unroll 1
   for (int it = 0; it < kVecPerThread / U; ++it) {
     int e[U], n[U];
@@ -664,23 +691,7 @@ __device__ __forceinline__ void adamw_tile(float* x, float* m1, float* m2, const
 #pragma unroll
     for (int k = 0; k < U; ++k) {
       f4 xn, an, sn;
-      const float* xs = reinterpret_cast<const float*>(&xv[k]);
-      const float* as = reinterpret_cast<const float*>(&av[k]);
-      const float* ss = reinterpret_cast<const float*>(&sv[k]);
-      const float* gs = reinterpret_cast<const float*>(&gv[k]);
-      float* xo = reinterpret_cast<float*>(&xn);
-      float* ao = reinterpret_cast<float*>(&an);
-      float* so = reinterpret_cast<float*>(&sn);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float xd = __builtin_fmaf(-lr * wd, xs[i], xs[i]);
-        const float a = __builtin_fmaf(b1, as[i], (1.0f - b1) * gs[i]);
-        const float q = __builtin_fmaf(b2, ss[i], (1.0f - b2) * gs[i] * gs[i]);
-        const float denom = __builtin_sqrtf(q * inv_bc2) + eps;
-        xo[i] = xd - lr * (a * inv_bc1) / denom;
-        ao[i] = a;
-        so[i] = q;
-      }
+      adamw_vec(xv[k], av[k], sv[k], gv[k], hp, xn, an, sn);
       store4_stream<FULL>(m1 + e[k], an, n[k]);
       store4_stream<FULL>(m2 + e[k], sn, n[k]);
       store4_stream<FULL>(x + e[k], xn, n[k]);
@@ -692,9 +703,7 @@ template <int U>
 __global__ __launch_bounds__(kBlock) void k_adamw_step(const Tile* __restrict__ tiles, int nfull, int ntiles,
                                                        int gfull, int M, int T, float* const* __restrict__ xp,
                                                        float* const* __restrict__ ap, float* const* __restrict__ sp,
-                                                       const float* const* __restrict__ gp, float lr, float b1,
-                                                       float b2, float eps, float wd, float inv_bc1,
-                                                       float inv_bc2) {
+                                                       const float* const* __restrict__ gp, const AdamHyper hp) {
   const bool full = static_cast<int>(blockIdx.x) < gfull;
   const long long base = full ? 0 : nfull;
   const long long count = full ? nfull : ntiles - nfull;
@@ -708,9 +717,81 @@ __global__ __launch_bounds__(kBlock) void k_adamw_step(const Tile* __restrict__ 
     float* a = ap[slot] + tl.offset;
     float* q = sp[slot] + tl.offset;
     const float* g = gp[slot] + tl.offset;
-    if (full) adamw_tile<U, true>(x, a, q, g, tl.count, lr, b1, b2, eps, wd, inv_bc1, inv_bc2);
-    else adamw_tile<U, false>(x, a, q, g, tl.count, lr, b1, b2, eps, wd, inv_bc1, inv_bc2);
+    if (full) adamw_tile<U, true>(x, a, q, g, tl.count, hp);
+    else adamw_tile<U, false>(x, a, q, g, tl.count, hp);
   }
+}
+
+// Sweep 1 of the round with the AdamW step folded in: read x, m1, m2, g of all M workers, step,
+// write m1, m2 and the stepped x (unlike SGD it cannot be rebuilt later from one extra read),
+// accumulate the squared distances of the stepped x.  28 bytes per replica-parameter; the plain
+// sweep 2 follows (8 bytes): 36 instead of 40.
+template <int M, int U, bool FULL>
+__device__ __forceinline__ void adamw_reduce_tile(const Tile tl, int T, float* const* __restrict__ xp,
+                                                  float* const* __restrict__ ap, float* const* __restrict__ sp,
+                                                  const float* const* __restrict__ gp, const AdamHyper hp,
+                                                  float inv_m, double (&acc)[M]) {
+  float part[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) part[m] = 0.f;
+#pragma unroll 1
+  for (int it = 0; it < kVecPerThread / U; ++it) {
+    int e[U], n[U];
+    f4 xv[U][M], av[U][M], sv[U][M], gv[U][M];
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      e[k] = 4 * (threadIdx.x + (it * U + k) * kBlock);
+      n[k] = FULL ? 4 : tl.count - e[k];
+#pragma unroll
+      for (int m = 0; m < M; ++m) {
+        const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
+        xv[k][m] = load4_stream<FULL>(xp[slot] + tl.offset + e[k], n[k]);
+        av[k][m] = load4_stream<FULL>(ap[slot] + tl.offset + e[k], n[k]);
+        sv[k][m] = load4_stream<FULL>(sp[slot] + tl.offset + e[k], n[k]);
+        gv[k][m] = load4_stream<FULL>(gp[slot] + tl.offset + e[k], n[k]);
+      }
+    }
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+#pragma unroll
+      for (int m = 0; m < M; ++m) {
+        const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
+        f4 xn, an, sn;
+        adamw_vec(xv[k][m], av[k][m], sv[k][m], gv[k][m], hp, xn, an, sn);
+        store4_stream<FULL>(ap[slot] + tl.offset + e[k], an, n[k]);
+        store4_stream<FULL>(sp[slot] + tl.offset + e[k], sn, n[k]);
+        store4<FULL>(xp[slot] + tl.offset + e[k], xn, n[k]);     // read again by sweep 2
+        xv[k][m] = xn;
+      }
+      const f4 mo = mean_offset<M>(xv[k], inv_m);
+#pragma unroll
+      for (int m = 0; m < M; ++m) part[m] = sumsq4((xv[k][m] - xv[k][0]) - mo, part[m]);
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < M; ++m) acc[m] += static_cast<double>(part[m]);
+}
+
+template <int M, int U>
+__global__ __launch_bounds__(kBlock) void k_adamw_reduce(const Tile* __restrict__ tiles, int nfull, int ntiles,
+                                                         int gfull, int T, float* const* __restrict__ xp,
+                                                         float* const* __restrict__ ap,
+                                                         float* const* __restrict__ sp,
+                                                         const float* const* __restrict__ gp, const AdamHyper hp,
+                                                         double* __restrict__ partials, int pstride) {
+  double acc[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) acc[m] = 0.0;
+  const float inv_m = 1.0f / static_cast<float>(M);
+  const TileWalk w = tile_walk(nfull, ntiles, gfull);
+  if (w.full) {
+    for (int t = w.first; t < w.end; t += w.stride)
+      adamw_reduce_tile<M, U, true>(tiles[t], T, xp, ap, sp, gp, hp, inv_m, acc);
+  } else {
+    for (int t = w.first; t < w.end; t += w.stride)
+      adamw_reduce_tile<M, U, false>(tiles[t], T, xp, ap, sp, gp, hp, inv_m, acc);
+  }
+  block_sums_store<M>(acc, partials + static_cast<size_t>(blockIdx.x) * pstride);
 }
 
 // ------------------------------------------------ by-products the paper logs every round
@@ -1189,6 +1270,26 @@ int scratch_xbar_table(dppf_plan* p, hipStream_t s, const void*** dev_out) {
   return table_upload(p, dppf_plan::RXBAR_SCRATCH, host.data(), host.size(), s, dev_out);
 }
 
+// Adam's hyper-parameters as the kernels take them; the bias corrections 1 - beta^t are formed in
+// double on the host.
+AdamHyper adam_hyper(float lr, float beta1, float beta2, float eps, float wd, long long step) {
+  const double bc1 = 1.0 - std::pow(static_cast<double>(beta1), static_cast<double>(step));
+  const double bc2 = 1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(step));
+  return AdamHyper{lr, beta1, beta2, eps, wd, static_cast<float>(1.0 / bc1), static_cast<float>(1.0 / bc2)};
+}
+
+int launch_adamw_step(dppf_plan* p, const void** xd, const void** ad, const void** sd, const void** gd,
+                      const AdamHyper hp, hipStream_t s) {
+  auto kern = k_adamw_step<2>;
+  int grid = 0, gfull = 0, rc;
+  if ((rc = grid_for(p, kern, p->M, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
+  if ((rc = timing_begin(p, DPPF_K_ADAMW_STEP, s))) return rc;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M, p->T,
+                     (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), hp);
+  HIP_TRY(hipGetLastError());
+  return timing_end(p, s);
+}
+
 // Shared body of dppf_pull_push_round and dppf_round (with_step).
 int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, const float* const* g,
                float lr, float mu, float wd, float pull, float push, float* r_out, float* c_out,
@@ -1514,17 +1615,43 @@ int dppf_local_adamw_step(dppf_plan* p, float* const* x, float* const* m1, float
   if ((rc = table_upload(p, dppf_plan::RM2, reinterpret_cast<const void* const*>(m2), n, s, &sd))) return rc;
   if ((rc = table_upload(p, dppf_plan::RG, reinterpret_cast<const void* const*>(g), n, s, &gd))) return rc;
   if (p->ntiles == 0) return DPPF_OK;
-  // bias corrections 1 - beta^t in double on the host
-  const double bc1 = 1.0 - std::pow(static_cast<double>(beta1), static_cast<double>(step));
-  const double bc2 = 1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(step));
-  auto kern = k_adamw_step<2>;
+  const AdamHyper hp = adam_hyper(lr, beta1, beta2, eps, weight_decay, step);
+  return launch_adamw_step(p, xd, ad, sd, gd, hp, s);
+} DPPF_CATCH
+
+int dppf_round_adamw(dppf_plan* p, float* const* x, float* const* m1, float* const* m2, const float* const* g,
+                     float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step, float pull,
+                     float push, float* r_out, float* c_out, void* stream) try {
+  if (!p || !x || !m1 || !m2 || !g || step < 1) return DPPF_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t n = static_cast<size_t>(p->M) * p->T;
+  const void **xd = nullptr, **ad = nullptr, **sd = nullptr, **gd = nullptr;
+  int rc;
+  if ((rc = table_upload(p, dppf_plan::RX, reinterpret_cast<const void* const*>(x), n, s, &xd))) return rc;
+  if ((rc = table_upload(p, dppf_plan::RM1, reinterpret_cast<const void* const*>(m1), n, s, &ad))) return rc;
+  if ((rc = table_upload(p, dppf_plan::RM2, reinterpret_cast<const void* const*>(m2), n, s, &sd))) return rc;
+  if ((rc = table_upload(p, dppf_plan::RG, reinterpret_cast<const void* const*>(g), n, s, &gd))) return rc;
+  if (p->ntiles == 0) return launch_finalize(p, 0, pull, push, true, r_out, c_out, s);
+  const AdamHyper hp = adam_hyper(lr, beta1, beta2, eps, weight_decay, step);
+  if (p->M > kMaxTemplM) {   // no register-resident kernel for this many workers: step, then the round
+    if ((rc = launch_adamw_step(p, xd, ad, sd, gd, hp, s))) return rc;
+    return round_impl(p, false, x, nullptr, nullptr, 0.f, 0.f, 0.f, pull, push, r_out, c_out, nullptr, s);
+  }
   int grid = 0, gfull = 0;
-  if ((rc = grid_for(p, kern, p->M, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
-  if ((rc = timing_begin(p, DPPF_K_ADAMW_STEP, s))) return rc;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M, p->T,
-                     (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), lr,
-                     beta1, beta2, eps, weight_decay, static_cast<float>(1.0 / bc1), static_cast<float>(1.0 / bc2));
+  if ((rc = timing_begin(p, DPPF_K_ADAMW_REDUCE, s))) return rc;
+  DPPF_SWITCH_M(p->M, {
+    constexpr int kU = kM <= 2 ? 2 : 1;     // 4*M*U <= 32 vectors in flight
+    auto kern = k_adamw_reduce<kM, kU>;
+    if ((rc = grid_for(p, kern, 1, kBlocksPerCUHeavyMath, &gfull, &grid))) return rc;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T,
+                       (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), hp,
+                       p->partials, p->M);
+  })
   HIP_TRY(hipGetLastError());
+  if ((rc = timing_end(p, s))) return rc;
+  if ((rc = timing_begin(p, DPPF_K_UPDATE, s))) return rc;
+  if ((rc = launch_sweep2<0, false, true>(p, p->M, xd, nullptr, nullptr, 0.f, 0, grid, pull, push, r_out, c_out, s)))
+    return rc;
   return timing_end(p, s);
 } DPPF_CATCH
 

@@ -14,7 +14,8 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "li
 _lib = None
 
 KERNEL_NAMES = {0: "reduce", 1: "step_reduce", 2: "finalize", 3: "update", 4: "local_step", 5: "mean",
-                6: "step_update", 7: "update_exact", 8: "seq_reduce", 9: "seq_update", 10: "adamw_step"}
+                6: "step_update", 7: "update_exact", 8: "seq_reduce", 9: "seq_update", 10: "adamw_step",
+                11: "adamw_reduce"}
 
 
 class DppfError(RuntimeError):
@@ -53,6 +54,7 @@ def load():
         "dppf_pull_push_round_exact": (ctypes.c_int, [vp, c_fpp, f, f, vp, vp, vp]),
         "dppf_pull_then_push": (ctypes.c_int, [vp, c_fpp, c_fpp, f, f, ctypes.c_int, vp, vp]),
         "dppf_local_adamw_step": (ctypes.c_int, [vp, c_fpp, c_fpp, c_fpp, c_fpp, f, f, f, f, f, i64, vp]),
+        "dppf_round_adamw": (ctypes.c_int, [vp, c_fpp, c_fpp, c_fpp, c_fpp, f, f, f, f, f, i64, f, f, vp, vp, vp]),
         "dppf_round_statistics": (ctypes.c_int, [vp, ctypes.c_int, f, f, vp, vp]),
         "dppf_push_schedule": (f, [ctypes.c_int, f, i64, i64]),
         "dppf_util_copy": (ctypes.c_int, [vp, vp, i64, vp]),
@@ -214,6 +216,15 @@ class Plan:
             self._expect(tab, self.M * self.T, name)
         _check(self._lib.dppf_local_adamw_step(self._h, x.ptr, m1.ptr, m2.ptr, g.ptr, lr, beta1, beta2, eps,
                                                weight_decay, step, _stream(stream)), "dppf_local_adamw_step")
+
+    def round_adamw(self, x, m1, m2, g, lr, beta1, beta2, eps, weight_decay, step, pull, push, r_out=None,
+                    c_out=None, stream=None) -> None:
+        x, m1, m2, g = _table(x), _table(m1), _table(m2), _table(g)
+        for tab, name in ((x, "x"), (m1, "m1"), (m2, "m2"), (g, "g")):
+            self._expect(tab, self.M * self.T, name)
+        _check(self._lib.dppf_round_adamw(self._h, x.ptr, m1.ptr, m2.ptr, g.ptr, lr, beta1, beta2, eps,
+                                          weight_decay, step, pull, push, _dev(r_out), _dev(c_out),
+                                          _stream(stream)), "dppf_round_adamw")
 
     # ---- flat forms (T == 1); x, v, g are [M, ld] tensors or raw device addresses
     def pull_push_round_flat(self, x, ld, pull, push, r_out=None, c_out=None, xbar_out=None, stream=None):

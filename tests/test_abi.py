@@ -87,3 +87,5 @@ def test_push_schedule_is_a_host_function(lib):
     assert lib.dppf_pull_then_push(None, None, None, 0.1, 0.1, 0, None, None) == -1
     assert lib.dppf_pull_push_round_exact(None, None, 0.1, 0.1, None, None, None) == -1
     assert lib.dppf_local_adamw_step(None, None, None, None, None, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == -1
+    assert lib.dppf_round_adamw(None, None, None, None, None, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 0.1, 0.1, None, None,
+                                None) == -1

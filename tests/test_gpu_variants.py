@@ -135,6 +135,48 @@ def test_adamw_local_step(M):
     plan.close()
 
 
+@pytest.mark.parametrize("M", [2, 4, 8, 9])
+def test_fused_adamw_round(M):
+    # the ViT runs of the paper: AdamW local steps, then the pull-push round
+    spec = W.small_spec(M=M, seed=520 + M)
+    inp = W.make_inputs(spec)
+    lr, b1, b2, eps, wd = f32(5e-4), f32(0.9), f32(0.999), f32(1e-8), f32(0.01)
+    pull, push = f32(0.9), f32(0.05)
+    x, m1, m2 = _rows(inp, inp.x), _rows(inp, inp.v), _rows(inp, inp.v)
+    xo = np.stack(inp.x).astype(np.float64)
+    ao, so = np.zeros_like(xo), np.zeros_like(xo)
+    plan = dppf.Plan(M, spec.numel)
+    r = torch.zeros(M, device="cuda")
+    c = torch.zeros(M, device="cuda")
+    for k in range(2):                                   # two plain steps, then the fused one
+        gk = inp.grads(k)
+        plan.local_adamw_step(x, m1, m2, _rows(inp, gk), lr, b1, b2, eps, wd, k + 1)
+        xo, ao, so = O.local_adamw_step(xo, ao, so, np.stack(gk), lr, b1, b2, eps, wd, k + 1)
+    gk = inp.grads(2)
+    g = _rows(inp, gk)
+    # unfused twin on copies, for the bit-for-bit claim
+    x2 = [[t.clone() for t in row] for row in x]
+    a2 = [[t.clone() for t in row] for row in m1]
+    s2 = [[t.clone() for t in row] for row in m2]
+    plan.round_adamw(x, m1, m2, g, lr, b1, b2, eps, wd, 3, pull, push, r_out=r, c_out=c)
+    x_pre, ao, so = O.local_adamw_step(xo, ao, so, np.stack(gk), lr, b1, b2, eps, wd, 3)
+    ref_x, ref_r, ref_c, _ = O.pull_push_round(x_pre, pull, push)
+    got = download_rows(x)
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+    assert_rel(c.cpu().numpy(), ref_c, 1e-4, "c")
+    assert_params_close(got, ref_x, inp.offsets, 6, "x", c=ref_c)
+    assert_params_close(download_rows(m1), ao, inp.offsets, 6, "m1")
+    assert_params_close(download_rows(m2), so, inp.offsets, 6, "m2")
+    assert_update_close(got, ref_x, x_pre, "fused adamw round")
+    twin = dppf.Plan(M, spec.numel)
+    twin.local_adamw_step(x2, a2, s2, g, lr, b1, b2, eps, wd, 3)
+    twin.pull_push_round(x2, pull, push)
+    assert np.array_equal(download_rows(x2), got)
+    assert np.array_equal(download_rows(a2), download_rows(m1))
+    plan.close()
+    twin.close()
+
+
 def test_round_statistics_and_schedule():
     M = 5
     r_host = np.array([5.0, 5.0, 8.0, 0.0, 1.5], np.float32)
