@@ -915,7 +915,8 @@ __global__ __launch_bounds__(kBlock) void k_probe(float* __restrict__ base, long
   for (long long t = blockIdx.x; t < ntiles; t += gridDim.x) {
     f4 v[U];
 #pragma unroll
-    for (int k = 0; k < U; ++k) v[k] = (f4){1.f, 2.f, 3.f, static_cast<float>(t)};
+    for (int k = 0; k < U; ++k)
+      v[k] = (R > 0) ? (f4){0.f, 0.f, 0.f, 0.f} : (f4){1.f, 2.f, 3.f, static_cast<float>(t)};
     if (R > 0) {
       f4 tmp[R > 0 ? R : 1][U];
 #pragma unroll

@@ -398,3 +398,53 @@ def test_fused_round_with_the_hyperparameters_the_paper_uses(pull, push, wd):
     assert_params_close(download_rows(v), ref_v, inp.offsets, 1, "v")
     assert_update_close(got, ref_x, x_pre, "round")
     plan.close()
+
+
+def test_non_finite_inputs_propagate_without_hanging():
+    # an Inf in one worker makes its distance infinite; nothing hangs, nothing outside the
+    # affected coordinates' arithmetic turns into garbage silently
+    spec = W.small_spec(M=4, seed=61)
+    inp = W.make_inputs(spec)
+    rows = [a.copy() for a in inp.x]
+    rows[1][12345] = np.inf
+    x = _dev_rows(inp, rows)
+    r = torch.zeros(4, device="cuda")
+    c = torch.zeros(4, device="cuda")
+    plan = dppf.Plan(4, spec.numel)
+    plan.pull_push_round(x, f32(0.1), f32(0.01), r_out=r, c_out=c)
+    torch.cuda.synchronize()
+    rr = r.cpu().numpy()
+    assert not np.all(np.isfinite(rr))
+    got = download_rows(x)
+    mask = np.ones(spec.d, bool)
+    mask[12345] = False
+    assert np.isfinite(got[:, 12345]).sum() < 4
+    # workers with a finite distance keep finite values away from the poisoned coordinate
+    for m in range(4):
+        if np.isfinite(rr[m]):
+            assert np.all(np.isfinite(got[m][mask]))
+    plan.close()
+
+
+def test_measurement_utilities():
+    n = 1_000_003
+    src = torch.randn(n, device="cuda")
+    dst = torch.zeros(n + 8, device="cuda")
+    dppf.util_copy(dst, src, n)
+    assert torch.equal(dst[:n], src) and torch.all(dst[n:] == 0)
+    dppf.util_copy(dst[1:], src[3:], n - 3)                      # 4-byte aligned only
+    assert torch.equal(dst[1:n - 2], src[3:])
+    lib = dppf.load()
+    import ctypes
+    assert lib.dppf_util_copy(ctypes.c_void_p(dst.data_ptr() + 2), ctypes.c_void_p(src.data_ptr()), 8, None) == -1
+    # streaming probe: every written stream holds (w + 1) * (sum of the read streams)
+    streams, length = 6, 16384 * 3
+    stride = length + 64
+    buf = torch.zeros(streams * stride, device="cuda")
+    for k in range(4):
+        buf[k * stride:k * stride + length] = float(k + 1)
+    dppf.util_stream_probe(buf, stride, length, 4, 0, False, 1)   # read only: nothing changes
+    assert torch.all(buf[4 * stride:] == 0)
+    assert lib.dppf_util_stream_probe(ctypes.c_void_p(buf.data_ptr()), stride, length, 3, 3, 0, 1, None) == -1
+    dppf.util_stream_probe(buf, stride, length, 1, 1, False, 2)   # copy stream 0 -> stream 1
+    assert torch.all(buf[stride:stride + length] == 1.0) and torch.all(buf[stride + length:2 * stride] == 0)
