@@ -222,3 +222,50 @@ def test_many_rounds_driver_tracks_the_oracle_and_the_valley_width():
     width = final.cpu().numpy()
     assert np.all(np.abs(width - push / pull) < 0.15 * push / pull), width
     plan.close()
+
+
+@pytest.mark.parametrize("schedule", ["fixed", "increasing"])
+def test_alg1_loop_matches_the_oracle(schedule):
+    # Alg. 1 end to end through the loop helper: tau-step periods, scheduled push, final average
+    from paper_2507_20424_amd.training import DppfLoop
+    M, tau, iters = 4, 3, 12
+    spec = W.small_spec(M=M, seed=950, tau=tau, weight_decay=1e-3)
+    inp = W.make_inputs(spec)
+    lr, mu, wd, pull, push = f32(0.1), f32(0.9), f32(1e-3), f32(0.1), f32(0.02)
+    x, v = _rows(inp, inp.x), _rows(inp, inp.v)
+    g = _rows(inp, inp.v)
+    loop = DppfLoop(x, v, g, tau=tau, pull=pull, push=push, lr=lr, momentum=mu, weight_decay=wd,
+                    schedule=schedule, total_iterations=iters)
+    xo, vo = np.stack(inp.x).astype(np.float64), np.stack(inp.v).astype(np.float64)
+    host_g = {}
+
+    def grad_fn(t):
+        host_g[t] = inp.grads(t)
+        for m in range(M):
+            for j, dst in enumerate(g[m]):
+                lo, hi = int(inp.offsets[j]), int(inp.offsets[j + 1])
+                dst.copy_(torch.from_numpy(host_g[t][m][lo:hi]))
+
+    rounds = 0
+    for t in range(iters):
+        did_round = loop.step(grad_fn)
+        gk = np.stack(host_g[t])
+        if (t + 1) % tau == 0:
+            assert did_round
+            rounds += 1
+            lam = f32(O.push_schedule(schedule, push, t + 1, iters))
+            xo, vo, ro, co, _ = O.dppf_round(xo, vo, gk, lr, mu, wd, pull, lam)
+            mv, pull_strength, push_strength = loop.round_statistics()
+            st = O.round_statistics(ro, pull, lam)
+            assert_rel(mv, st["relaxed_mv"], 1e-4, "relaxed MV")
+            assert_rel(pull_strength, st["pull_strength"], 1e-4, "pull strength")
+            assert abs(push_strength - lam) <= 1e-7
+        else:
+            assert not did_round
+            xo, vo = O.local_sgd_step(xo, vo, gk, lr, mu, wd)
+    assert rounds == iters // tau
+    assert_params_close(download_rows(x), xo, inp.offsets, iters, "x after the loop")
+    avg = upload_tensors(np.zeros(spec.d, np.float32), inp.offsets)
+    loop.average(avg)
+    assert_params_close(download(avg)[None], O.replica_mean(xo)[None], inp.offsets, iters, "returned average")
+    loop.close()
