@@ -192,6 +192,8 @@ def main() -> int:
     for name, ms in recs:
         per_kernel.setdefault(name, []).append(ms)
     avg_ms = {k: sum(vv) / len(vv) for k, vv in per_kernel.items()}
+    min_ms = {k: min(vv) for k, vv in per_kernel.items()}
+    med_ms = {k: sorted(vv)[len(vv) // 2] for k, vv in per_kernel.items()}
     dominant = max(avg_ms, key=lambda k: avg_ms[k] * len(per_kernel[k]))     # most GPU time in total
     achieved = bytes_per_rp[dominant] * n_rp / (avg_ms[dominant] * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -220,6 +222,8 @@ def main() -> int:
         "effective_GBps": call_bytes[args.call] * value / 1e9,
         "effective_frac_of_hbm_peak": call_bytes[args.call] * value / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": avg_ms,
+        "kernel_ms_median": med_ms,
+        "kernel_ms_min": min_ms,
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
