@@ -43,8 +43,11 @@ CALL_BYTES = {"round": 28.0, "pull_push": 12.0, "local_step": 20.0, "pull_push_e
 
 
 def kernel_source_hash() -> str:
-    with open(os.path.join(ROOT, "paper_2507_20424_amd", "csrc", "dppf.hip"), "rb") as f:
-        return hashlib.sha256(f.read()).hexdigest()[:16]
+    h = hashlib.sha256()
+    for name in ("dppf_kernels.h", "dppf.hip"):
+        with open(os.path.join(ROOT, "paper_2507_20424_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
 
 
 def measured_traffic(kernel: str, workload: str):
