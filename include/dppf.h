@@ -25,6 +25,8 @@
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *    ENQUEUE work on it and return without waiting for the GPU.  A plan must not be used
  *    from two streams or two host threads at the same time (it owns scratch buffers).
+ *  - Calls may be captured into a HIP graph, provided one eager call with the same pointer
+ *    tables was made before (a new table is uploaded with an event wait that capture forbids).
  *  - Small outputs r_out / c_out are DEVICE arrays of M floats, written by the enqueued work.
  *  - Return value: DPPF_OK (0) or a negative DPPF_E* code.  No exceptions, no aborts.
  *    Arguments are validated before anything is enqueued; on error nothing was launched.
