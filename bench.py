@@ -94,7 +94,7 @@ def main() -> int:
     ap.add_argument("--cpu-sample-cols", type=int, default=1_000_000_000)
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU (the M workers are M replicas resident in one GPU's "
+        print("bench.py: the library runs on one GPU (the M workers are M replicas resident in one GPU's "
               "HBM); --gpus must be 1", file=sys.stderr)
         return 2
 
