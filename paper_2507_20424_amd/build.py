@@ -13,6 +13,8 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 SRC = os.path.join(PKG_DIR, "csrc", "dppf.hip")
 LIB = os.path.join(PKG_DIR, "csrc", "libdppf.so")
+CLI_SRC = os.path.join(PKG_DIR, "csrc", "dppf_cli.c")
+CLI = os.path.join(PKG_DIR, "csrc", "dppf_cli")
 INCLUDE = os.path.join(ROOT, "include")
 
 HIPCC_FLAGS = [
@@ -45,6 +47,29 @@ def build_library(verbose: bool = True) -> str:
     return LIB
 
 
+def build_cli(verbose: bool = True) -> str:
+    """Compile csrc/dppf_cli.c -- plain C against the C ABI and the HIP runtime API -- with gcc."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    gcc = shutil.which("gcc") or "gcc"
+    cmd = [gcc, "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+           "-I", INCLUDE, "-o", CLI + ".tmp", CLI_SRC, "-L", os.path.dirname(LIB), "-ldppf",
+           "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("gcc failed:\n" + res.stdout)
+    if verbose and res.stdout.strip():
+        print(res.stdout)
+    os.replace(CLI + ".tmp", CLI)
+    return CLI
+
+
+def build_all(verbose: bool = True) -> None:
+    build_library(verbose)
+    build_cli(verbose)
+
+
 if __name__ == "__main__":
-    build_library()
+    build_all()
     sys.exit(0)

@@ -89,3 +89,9 @@ def test_push_schedule_is_a_host_function(lib):
     assert lib.dppf_local_adamw_step(None, None, None, None, None, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == -1
     assert lib.dppf_round_adamw(None, None, None, None, None, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 0.1, 0.1, None, None,
                                 None) == -1
+
+
+def test_plain_c_client_builds_against_the_header():
+    from paper_2507_20424_amd import build as B
+    path = B.build_cli(verbose=False)
+    assert os.access(path, os.X_OK)
