@@ -212,7 +212,8 @@ int dppf_util_copy(float* dst, const float* src, int64_t n, void* stream);
  * arrays are k = reads..reads+writes-1, or k = 0..writes-1 when inplace != 0 (the lane that read
  * an element overwrites it).  Only elements below the largest multiple of the probe's tile are
  * touched.  Supported (reads, writes): (1,0) (4,0) (12,0) (0,1) (0,4) (1,1) and, with or without
- * inplace, (4,4) (8,4) (12,4) (12,8); anything else returns DPPF_EINVAL.  blocks_per_cu in 1..16.
+ * inplace, (4,4) (8,4) (12,4) (12,8), and in place only (16,8) (24,8); anything else returns
+ * DPPF_EINVAL.  blocks_per_cu in 1..16.
  * Timing is the caller's job (events around the call).  */
 int dppf_util_stream_probe(float* base, int64_t stride, int64_t n, int reads, int writes, int inplace,
                            int blocks_per_cu, void* stream);

@@ -868,6 +868,8 @@ int dppf_util_stream_probe(float* base, int64_t stride, int64_t n, int reads, in
   DPPF_PROBE(12, 4, 1, true)
   DPPF_PROBE(12, 8, 1, false)
   DPPF_PROBE(12, 8, 1, true)
+  DPPF_PROBE(16, 8, 1, true)
+  DPPF_PROBE(24, 8, 1, true)
 #undef DPPF_PROBE
   return DPPF_EINVAL;   // this read/write mix is not instantiated
 }
