@@ -448,3 +448,36 @@ def test_measurement_utilities():
     assert lib.dppf_util_stream_probe(ctypes.c_void_p(buf.data_ptr()), stride, length, 3, 3, 0, 1, None) == -1
     dppf.util_stream_probe(buf, stride, length, 1, 1, False, 2)   # copy stream 0 -> stream 1
     assert torch.all(buf[stride:stride + length] == 1.0) and torch.all(buf[stride + length:2 * stride] == 0)
+
+
+@pytest.mark.parametrize("M", [12, 17])
+def test_many_workers_on_a_list_that_fills_the_chip(M):
+    # M > 8 goes through a stored average and groups of up to 8 workers; here with more tiles than
+    # compute units, so the groups' launches must share one layout of the partial sums
+    spec = W.small_spec(M=M, seed=900 + M, shapes=((1_300_000,), (777,), (1_200_003,), (5,)))
+    h = _hyper(spec)
+    inp = W.make_inputs(spec)
+    gk = inp.grads(0)
+    x, v, g = _dev_rows(inp, inp.x), _dev_rows(inp, inp.v), _dev_rows(inp, gk)
+    r = torch.zeros(M, device="cuda")
+    c = torch.zeros(M, device="cuda")
+    xbar = upload_tensors(np.zeros(spec.d, np.float32), inp.offsets)
+    plan = dppf.Plan(M, spec.numel)
+    plan.round(x, v, g, h["lr"], h["mu"], h["wd"], h["pull"], h["push"], r_out=r, c_out=c, xbar_out=xbar)
+    x_pre, _ = O.local_sgd_step(np.stack(inp.x), np.stack(inp.v), np.stack(gk), h["lr"], h["mu"], h["wd"])
+    ref_x, ref_v, ref_r, ref_c, ref_avg = O.dppf_round(np.stack(inp.x), np.stack(inp.v), np.stack(gk), h["lr"],
+                                                       h["mu"], h["wd"], h["pull"], h["push"])
+    got = download_rows(x)
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+    assert_rel(c.cpu().numpy(), ref_c, 1e-4, "c")
+    assert_params_close(got, ref_x, inp.offsets, 1, "x")
+    assert_params_close(download_rows(v), ref_v, inp.offsets, 1, "v")
+    assert_params_close(download(xbar)[None], ref_avg[None], inp.offsets, 1, "xbar")
+    assert_update_close(got, ref_x, x_pre, "round")
+    # the same without asking for the average (the plan's own scratch vector is used)
+    x2 = _dev_rows(inp, inp.x)
+    r2 = torch.zeros(M, device="cuda")
+    plan.local_sgd_step(x2, _dev_rows(inp, inp.v), g, h["lr"], h["mu"], h["wd"])
+    plan.pull_push_round(x2, h["pull"], h["push"], r_out=r2)
+    assert np.array_equal(download_rows(x2), got) and np.array_equal(r2.cpu().numpy(), r.cpu().numpy())
+    plan.close()
