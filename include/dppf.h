@@ -75,6 +75,16 @@ int dppf_plan_destroy(dppf_plan* plan);
 /* d = sum of numel. */
 int64_t dppf_plan_dim(const dppf_plan* plan);
 
+/* HOST-ONLY, needs no GPU: the work decomposition a plan would use for this tensor list.  Every
+ * tensor is cut into tiles of at most DPPF_TILE_ELEMS consecutive elements; the list holds all
+ * full tiles first (in list order), then the partial ones (tensor tails, small tensors).
+ * Writes d = sum numel, the number of full tiles and the total; if the three tile arrays are
+ * non-NULL (capacity `cap` entries, else DPPF_ELIMIT) also each tile's tensor index, first
+ * element inside that tensor, and element count.  */
+#define DPPF_TILE_ELEMS 4096
+int dppf_layout_tiles(int T, const int64_t* numel, int64_t* d, int64_t* nfull, int64_t* ntiles, int64_t cap,
+                      int32_t* tile_tensor, int64_t* tile_offset, int32_t* tile_count);
+
 /* ---------------------------------------------------------------------------------------
  * Steps of the round (Alg. 1 consensus branch with x_C = x_A; Sec. 5 Eq. 5).
  * ------------------------------------------------------------------------------------- */

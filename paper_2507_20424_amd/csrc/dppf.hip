@@ -37,6 +37,8 @@
 #include "dppf.h"
 #include "dppf_kernels.h"
 
+static_assert(kTileElems == DPPF_TILE_ELEMS, "the header documents the tile size");
+
 namespace {
 
 // =========================================================================== host side
@@ -366,6 +368,39 @@ int scratch_xbar_table(dppf_plan* p, hipStream_t s, const void*** dev_out) {
   return table_upload(p, dppf_plan::RXBAR_SCRATCH, host.data(), host.size(), s, dev_out);
 }
 
+// The tile list of a tensor list: every tensor cut into pieces of kTileElems elements, full
+// pieces first (list order kept), then the partial ones.  Pure host code.
+int build_tile_list(int T, const int64_t* numel, std::vector<Tile>* tiles, int* nfull, long long* d,
+                    std::vector<long long>* tensor_offset) {
+  try {
+    std::vector<Tile> all;
+    tensor_offset->assign(static_cast<size_t>(T) + 1, 0);
+    long long total = 0;
+    for (int t = 0; t < T; ++t) {
+      if (numel[t] < 0) return DPPF_EINVAL;
+      (*tensor_offset)[t] = total;
+      total += numel[t];
+      for (long long off = 0; off < numel[t]; off += kTileElems) {
+        const long long left = numel[t] - off;
+        all.push_back(Tile{off, t, static_cast<int>(left < kTileElems ? left : kTileElems)});
+      }
+      if (all.size() > static_cast<size_t>(INT32_MAX / 2)) return DPPF_ELIMIT;
+    }
+    (*tensor_offset)[T] = total;
+    tiles->clear();
+    tiles->reserve(all.size());
+    for (const Tile& t : all)
+      if (t.count == kTileElems) tiles->push_back(t);
+    *nfull = static_cast<int>(tiles->size());
+    for (const Tile& t : all)
+      if (t.count != kTileElems) tiles->push_back(t);
+    *d = total;
+  } catch (const std::bad_alloc&) {
+    return DPPF_ENOMEM;
+  }
+  return DPPF_OK;
+}
+
 // Adam's hyper-parameters as the kernels take them; the bias corrections 1 - beta^t are formed in
 // double on the host.
 AdamHyper adam_hyper(float lr, float beta1, float beta2, float eps, float wd, long long step) {
@@ -502,37 +537,13 @@ int dppf_plan_create(dppf_plan** out, int M, int T, const int64_t* numel) {
   std::vector<Tile> tiles;
   p->M = M;
   p->T = T;
-  try {
-    p->numel.resize(static_cast<size_t>(T));
-    p->tensor_offset.resize(static_cast<size_t>(T) + 1, 0);
-    for (int t = 0; t < T; ++t) {
-      if (numel[t] < 0) { delete p; return DPPF_EINVAL; }
-      p->numel[t] = numel[t];
-      p->tensor_offset[t] = p->d;
-      p->d += numel[t];
-      for (long long off = 0; off < numel[t]; off += kTileElems) {
-        const long long left = numel[t] - off;
-        tiles.push_back(Tile{off, t, static_cast<int>(left < kTileElems ? left : kTileElems)});
-      }
-      if (tiles.size() > static_cast<size_t>(INT32_MAX / 2)) { delete p; return DPPF_ELIMIT; }
-    }
-    p->tensor_offset[T] = p->d;
-  } catch (const std::bad_alloc&) {
-    delete p;
-    return DPPF_ENOMEM;
-  }
-  {   // full tiles first (list order kept inside each group)
-    std::vector<Tile> ordered;
-    try {
-      ordered.reserve(tiles.size());
-      for (const Tile& t : tiles) if (t.count == kTileElems) ordered.push_back(t);
-      p->nfull = static_cast<int>(ordered.size());
-      for (const Tile& t : tiles) if (t.count != kTileElems) ordered.push_back(t);
-    } catch (const std::bad_alloc&) {
+  {
+    const int rc = build_tile_list(T, numel, &tiles, &p->nfull, &p->d, &p->tensor_offset);
+    if (rc != DPPF_OK) {
       delete p;
-      return DPPF_ENOMEM;
+      return rc;
     }
-    tiles.swap(ordered);
+    p->numel.assign(numel, numel + T);
   }
   p->ntiles = static_cast<int>(tiles.size());
 
@@ -574,6 +585,29 @@ int dppf_plan_create(dppf_plan** out, int M, int T, const int64_t* numel) {
 }
 
 int64_t dppf_plan_dim(const dppf_plan* p) { return p ? p->d : 0; }
+
+int dppf_layout_tiles(int T, const int64_t* numel, int64_t* d, int64_t* nfull, int64_t* ntiles, int64_t cap,
+                      int32_t* tile_tensor, int64_t* tile_offset, int32_t* tile_count) {
+  if (T < 0 || (T > 0 && !numel) || !d || !nfull || !ntiles || cap < 0) return DPPF_EINVAL;
+  std::vector<Tile> tiles;
+  std::vector<long long> offsets;
+  int full = 0;
+  long long total = 0;
+  const int rc = build_tile_list(T, numel, &tiles, &full, &total, &offsets);
+  if (rc != DPPF_OK) return rc;
+  *d = total;
+  *nfull = full;
+  *ntiles = static_cast<int64_t>(tiles.size());
+  if (tile_tensor && tile_offset && tile_count) {
+    if (cap < static_cast<int64_t>(tiles.size())) return DPPF_ELIMIT;
+    for (size_t i = 0; i < tiles.size(); ++i) {
+      tile_tensor[i] = tiles[i].tensor;
+      tile_offset[i] = tiles[i].offset;
+      tile_count[i] = tiles[i].count;
+    }
+  }
+  return DPPF_OK;
+}
 
 int dppf_replica_mean(dppf_plan* p, const float* const* x, float* const* xbar, void* stream) try {
   if (!p || !x || !xbar) return DPPF_EINVAL;

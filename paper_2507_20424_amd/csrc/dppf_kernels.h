@@ -12,7 +12,7 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 typedef f4 f4u __attribute__((aligned(4)));   // 16-byte vector that may sit on any 4-byte boundary
 
 constexpr int kBlock = 256;                   // threads per block (4 waves)
-constexpr int kTileElems = 4096;              // elements of ONE worker's tensor per tile
+constexpr int kTileElems = 4096;              // elements of ONE worker's tensor per tile (DPPF_TILE_ELEMS)
 constexpr int kVecPerThread = kTileElems / (4 * kBlock);   // 16-byte vectors per thread per tile
 constexpr int kMaxTemplM = 8;                 // worker counts with a register-resident kernel
 constexpr int kMaxBlocksPerCU = 8;             // upper bound on resident blocks per CU (sizes buffers)

@@ -43,6 +43,9 @@ def load():
         "dppf_plan_create": (ctypes.c_int, [ctypes.POINTER(vp), ctypes.c_int, ctypes.c_int, ctypes.POINTER(i64)]),
         "dppf_plan_destroy": (ctypes.c_int, [vp]),
         "dppf_plan_dim": (i64, [vp]),
+        "dppf_layout_tiles": (ctypes.c_int, [ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                             ctypes.POINTER(i64), i64, ctypes.POINTER(ctypes.c_int32),
+                                             ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_int32)]),
         "dppf_replica_mean": (ctypes.c_int, [vp, c_fpp, c_fpp, vp]),
         "dppf_dist_norms": (ctypes.c_int, [vp, c_fpp, c_fpp, vp, vp]),
         "dppf_pull_push_round": (ctypes.c_int, [vp, c_fpp, f, f, vp, vp, c_fpp, vp]),
@@ -276,3 +279,18 @@ def util_stream_probe(base, stride: int, n: int, reads: int, writes: int, inplac
     """Launch the library's streaming probe (measurement aid, see include/dppf.h)."""
     _check(load().dppf_util_stream_probe(_dev(base), stride, n, reads, writes, 1 if inplace else 0, blocks_per_cu,
                                          _stream(stream)), "dppf_util_stream_probe")
+
+
+def layout_tiles(numel: Sequence[int]):
+    """(d, nfull, tiles) for a tensor list; tiles = list of (tensor, offset, count).  Host only."""
+    lib = load()
+    T = len(numel)
+    arr = (ctypes.c_int64 * max(T, 1))(*[int(n) for n in numel])
+    d, nfull, ntiles = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    _check(lib.dppf_layout_tiles(T, arr, ctypes.byref(d), ctypes.byref(nfull), ctypes.byref(ntiles), 0, None, None,
+                                 None), "dppf_layout_tiles")
+    n = ntiles.value
+    tt, to, tc = (ctypes.c_int32 * max(n, 1))(), (ctypes.c_int64 * max(n, 1))(), (ctypes.c_int32 * max(n, 1))()
+    _check(lib.dppf_layout_tiles(T, arr, ctypes.byref(d), ctypes.byref(nfull), ctypes.byref(ntiles), n, tt, to, tc),
+           "dppf_layout_tiles")
+    return d.value, nfull.value, [(tt[i], to[i], tc[i]) for i in range(n)]

@@ -95,3 +95,34 @@ def test_plain_c_client_builds_against_the_header():
     from paper_2507_20424_amd import build as B
     path = B.build_cli(verbose=False)
     assert os.access(path, os.X_OK)
+
+
+def test_tile_layout_covers_every_element_exactly_once(lib):
+    from paper_2507_20424_amd import dppf, workloads as W
+    lists = [[], [0], [1], [4095], [4096], [4097], [3, 0, 8192, 1, 12289, 0, 5], list(W.SPECS["pyramidnet_M8"].numel),
+             list(W.SPECS["vitb16_M4"].numel)]
+    for numel in lists:
+        d, nfull, tiles = dppf.layout_tiles(numel)
+        assert d == sum(numel)
+        assert nfull == sum(n // 4096 for n in numel)
+        assert len(tiles) == sum(-(-n // 4096) for n in numel)
+        assert all(c == 4096 for _, _, c in tiles[:nfull])
+        assert all(0 < c < 4096 for _, _, c in tiles[nfull:])
+        covered = {}
+        for t, off, c in tiles:
+            assert 0 <= t < len(numel) and off % 4096 == 0 and off + c <= numel[t]
+            covered.setdefault(t, []).append((off, c))
+        for t, n in enumerate(numel):
+            pieces = sorted(covered.get(t, []))
+            assert sum(c for _, c in pieces) == n
+            assert [o for o, _ in pieces] == list(range(0, n, 4096))
+        # full tiles keep list order, partial tiles too
+        assert [t for t, _, _ in tiles[:nfull]] == sorted(t for t, _, _ in tiles[:nfull])
+        assert [t for t, _, _ in tiles[nfull:]] == sorted(t for t, _, _ in tiles[nfull:])
+    import ctypes
+    bad = (ctypes.c_int64 * 2)(5, -1)
+    out = ctypes.c_int64()
+    assert lib.dppf_layout_tiles(2, bad, ctypes.byref(out), ctypes.byref(out), ctypes.byref(out), 0, None, None,
+                                 None) == -1
+    assert lib.dppf_layout_tiles(1, None, ctypes.byref(out), ctypes.byref(out), ctypes.byref(out), 0, None, None,
+                                 None) == -1
