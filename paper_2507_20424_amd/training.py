@@ -42,10 +42,45 @@ class DppfLoop:
         self.c = torch.zeros(self.M, device=dev)          # coefficients alpha - lambda/r of that round
         self.stats = torch.zeros(2 * self.M + 1, device=dev)
         self.push_used = self.push
+        self._params = None                                # set by from_modules
+
+    @classmethod
+    def from_modules(cls, modules: Sequence, **kwargs) -> "DppfLoop":
+        """M replicas of one torch.nn.Module on the same GPU (identical parameter lists).  The
+        parameters are updated in place; gradients are read from ``p.grad`` after the caller's
+        backward passes, wherever autograd put them (the gradient pointer table is rebuilt every
+        iteration); momentum buffers are created here."""
+        import torch
+        params = [[p for p in mod.parameters() if p.requires_grad] for mod in modules]
+        shapes = [tuple(p.shape) for p in params[0]]
+        for row in params:
+            if [tuple(p.shape) for p in row] != shapes:
+                raise ValueError("the replicas must have identical parameter lists")
+            for p in row:
+                if not p.is_contiguous() or p.dtype != torch.float32:
+                    raise ValueError("parameters must be contiguous float32 tensors")
+        x = [[p.data for p in row] for row in params]
+        v = [[torch.zeros_like(p.data) for p in row] for row in params]
+        g = [[torch.zeros_like(p.data) for p in row] for row in params]     # placeholders until backward ran
+        loop = cls(x, v, g, **kwargs)
+        loop._params = params
+        return loop
+
+    def _gradients_from_autograd(self) -> None:
+        rows = []
+        for row in self._params:
+            for p in row:
+                if p.grad is None or not p.grad.is_contiguous():
+                    raise ValueError("every parameter needs a contiguous .grad before step()")
+            rows.append([p.grad for p in row])
+        self.g = rows
+        self.gt = dppf.PointerTable(rows)
 
     def step(self, grad_fn: Callable[[int], None], lr: Optional[float] = None) -> bool:
         """One iteration of Alg. 1 for all workers.  Returns True if it ended with a round."""
         grad_fn(self.t)
+        if self._params is not None:
+            self._gradients_from_autograd()
         eta = self.lr if lr is None else float(lr)
         self.t += 1
         if self.t % self.tau != 0:

@@ -269,3 +269,51 @@ def test_alg1_loop_matches_the_oracle(schedule):
     loop.average(avg)
     assert_params_close(download(avg)[None], O.replica_mean(xo)[None], inp.offsets, iters, "returned average")
     loop.close()
+
+
+def test_alg1_loop_on_torch_modules_with_autograd_gradients():
+    # M replicas of a small network, real backward passes on synthetic regression data; the
+    # parameters move through the library, the oracle follows with the downloaded gradients
+    from paper_2507_20424_amd.training import DppfLoop
+    torch.manual_seed(0)
+    M, tau, iters = 4, 2, 6
+    lr, mu, wd, pull, push = f32(0.05), f32(0.9), f32(1e-4), f32(0.5), f32(0.05)
+
+    def make():
+        return torch.nn.Sequential(torch.nn.Linear(13, 37), torch.nn.Tanh(), torch.nn.Linear(37, 5)).cuda()
+
+    models = [make() for _ in range(M)]
+    with torch.no_grad():                                   # Alg. 1: one random init, distributed to all
+        for mod in models[1:]:
+            for p, q in zip(mod.parameters(), models[0].parameters()):
+                p.copy_(q)
+    data = [(torch.randn(64, 13, device="cuda"), torch.randn(64, 5, device="cuda")) for _ in range(M)]
+    loop = DppfLoop.from_modules(models, tau=tau, pull=pull, push=push, lr=lr, momentum=mu, weight_decay=wd)
+
+    def flat(rows):
+        return np.stack([torch.cat([t.reshape(-1) for t in row]).cpu().numpy() for row in rows])
+
+    xo = flat(loop.x).astype(np.float64)
+    vo = np.zeros_like(xo)
+    numel = [int(t.numel()) for t in loop.x[0]]
+    offsets = np.concatenate([[0], np.cumsum(numel)])
+
+    def backward(_t):
+        for mod, (inp_, tgt) in zip(models, data):
+            mod.zero_grad(set_to_none=True)                 # fresh gradient tensors every iteration
+            torch.nn.functional.mse_loss(mod(inp_), tgt).backward()
+
+    for t in range(iters):
+        did_round = loop.step(backward)
+        go = flat(loop.g)
+        if did_round:
+            xo, vo, ro, _, _ = O.dppf_round(xo, vo, go, lr, mu, wd, pull, push)
+            assert_rel(loop.r.cpu().numpy(), ro, 1e-4, "r")
+        else:
+            xo, vo = O.local_sgd_step(xo, vo, go, lr, mu, wd)
+        # the modules' own parameters are the library's x: compare after every iteration, so the
+        # oracle is always fed gradients taken at (numerically) the same point
+        got = flat([[p.data for p in mod.parameters()] for mod in models])
+        assert_params_close(got, xo, offsets, t + 1, f"parameters after iteration {t}")
+        xo = got.astype(np.float64)                          # re-anchor: gradients depend on x itself
+    loop.close()
