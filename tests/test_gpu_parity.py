@@ -481,3 +481,46 @@ def test_many_workers_on_a_list_that_fills_the_chip(M):
     plan.pull_push_round(x2, h["pull"], h["push"], r_out=r2)
     assert np.array_equal(download_rows(x2), got) and np.array_equal(r2.cpu().numpy(), r.cpu().numpy())
     plan.close()
+
+
+@pytest.mark.parametrize("case", range(12))
+def test_random_lists_with_mixed_alignment(case):
+    # random tensor counts and sizes; every (worker, role, tensor) gets its own misalignment of
+    # 0..3 elements, so the replicas of one tensor sit at different offsets modulo 16 bytes
+    rng = np.random.default_rng(4000 + case)
+    M = int(rng.integers(1, 10))
+    T = int(rng.integers(1, 9))
+    sizes = [int(rng.choice([0, 1, 2, 3, 5, 63, 64, 1000, 4095, 4096, 4097, 8191, 20_000, 70_001])) for _ in range(T)]
+    spec = W.small_spec(M=M, seed=5000 + case, shapes=tuple((n,) for n in sizes), weight_decay=1e-3)
+    h = _hyper(spec)
+    inp = W.make_inputs(spec)
+    gk = inp.grads(0)
+
+    def scattered(arrays):
+        rows = []
+        for a in arrays:
+            row = []
+            for t in range(T):
+                lo, hi = int(inp.offsets[t]), int(inp.offsets[t + 1])
+                shift = int(rng.integers(0, 4))
+                buf = torch.empty(hi - lo + shift, dtype=torch.float32, device="cuda")
+                view = buf[shift:]
+                if hi > lo:
+                    view.copy_(torch.from_numpy(a[lo:hi]))
+                row.append(view)
+            rows.append(row)
+        return rows
+
+    x, v, g = scattered(inp.x), scattered(inp.v), scattered(gk)
+    r = torch.zeros(M, device="cuda")
+    c = torch.zeros(M, device="cuda")
+    plan = dppf.Plan(M, spec.numel)
+    plan.round(x, v, g, h["lr"], h["mu"], h["wd"], h["pull"], h["push"], r_out=r, c_out=c)
+    ref_x, ref_v, ref_r, ref_c, _ = O.dppf_round(np.stack(inp.x), np.stack(inp.v), np.stack(gk), h["lr"], h["mu"],
+                                                 h["wd"], h["pull"], h["push"])
+    if M > 1 and spec.d > 0:
+        assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+        assert_rel(c.cpu().numpy(), ref_c, 1e-4, "c")
+    assert_params_close(download_rows(x), ref_x, inp.offsets, 1, "x", c=ref_c)
+    assert_params_close(download_rows(v), ref_v, inp.offsets, 1, "v")
+    plan.close()
