@@ -130,8 +130,9 @@ int dppf_round(dppf_plan* plan, float* const* x, float* const* v, const float* c
  *   d_m = x_m - x_A;  x_m <- x_m - pull d_m + (push_r / M^2) (M d_m/||d_m|| - sum_j d_j/||d_j||).
  * push_r is the regulariser's own coefficient lambda_r (Eq. 5's lambda corresponds to push_r / M).
  * Workers at zero distance contribute a zero unit vector.  The average of the workers is
- * preserved.  r_out[m] = ||d_m||, c_out[m] = pull - (push_r/M)/r_m, both optional.  Same two
- * sweeps and the same memory traffic as dppf_pull_push_round.  M <= 8 (else DPPF_ELIMIT).  */
+ * preserved.  r_out[m] = ||d_m||, c_out[m] = pull - (push_r/M)/r_m, both optional.  For M <= 8
+ * the same two sweeps and the same memory traffic as dppf_pull_push_round; for more workers the
+ * average and the sum of unit vectors are staged in two plan-owned d-vectors.  */
 int dppf_pull_push_round_exact(dppf_plan* plan, float* const* x, float pull, float push_r,
                                float* r_out, float* c_out, void* stream);
 
@@ -141,7 +142,7 @@ int dppf_pull_push_round_exact(dppf_plan* plan, float* const* x, float pull, flo
  * (DPPF_PUSH_FROM_AVERAGE, Alg. 1) or x_C itself (DPPF_PUSH_FROM_CONSENSUS, the variant the
  * appendix remark on leader-based consensus describes).  A worker whose pulled gap is zero gets
  * no push.  r_post_out[m] (optional) = norm of the pulled gap.  With x_C = x_A and pull < 1 the
- * result equals dppf_pull_push_round.  M <= 8 (else DPPF_ELIMIT).  */
+ * result equals dppf_pull_push_round.  */
 enum { DPPF_PUSH_FROM_AVERAGE = 0, DPPF_PUSH_FROM_CONSENSUS = 1 };
 int dppf_pull_then_push(dppf_plan* plan, float* const* x, const float* const* x_c, float pull,
                         float push, int push_from, float* r_post_out, void* stream);

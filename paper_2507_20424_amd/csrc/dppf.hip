@@ -83,8 +83,9 @@ struct dppf_plan {
   int partials_rows = 0;
   Coef* coef = nullptr;         // [M]
   float* xbar_scratch = nullptr;            // d floats, only when M > kMaxTemplM
+  float* usum_scratch = nullptr;            // d floats, only when M > kMaxTemplM (exact update)
   std::vector<long long> tensor_offset;     // start of tensor t inside xbar_scratch
-  enum Role { RX = 0, RV, RG, RM1, RM2, RXBAR, RXBAR_SCRATCH, RXC, NROLES };
+  enum Role { RX = 0, RV, RG, RM1, RM2, RXBAR, RXBAR_SCRATCH, RUSUM_SCRATCH, RXC, NROLES };
   PtrTable tab[NROLES];
   // resident blocks per CU of each kernel that has been launched (queried once)
   std::vector<std::pair<const void*, int>> occupancy;
@@ -333,32 +334,61 @@ int launch_update_exact(dppf_plan* p, const void** xp, int nparts, float pull, f
   return DPPF_OK;
 }
 
-template <int REF>
-int launch_seq(dppf_plan* p, const void** xp, const void** xcp, float pull, float push, float* r_post_out,
-               hipStream_t s) {
-  float* const* x = (float* const*)(xp);
+// Sweep 1 (WRITE = false) or sweep 2 (WRITE = true) of dppf_pull_then_push over workers
+// [m0, m0+mg).  REF as in seq_tile; refp is the stored average for REF == 2.
+template <int REF, bool WRITE>
+int launch_seq(dppf_plan* p, int mg, int m0, const void** xp, const void** xcp, const void** refp, float pull,
+               float push, int nparts, float* r_post_out, GridShape* shape, hipStream_t s) {
+  float* const* x = (float* const*)(xp) + static_cast<size_t>(m0) * p->T;
   const float* const* xc = (const float* const*)(xcp);
+  const float* const* rf = (const float* const*)(refp);
   const float keep = static_cast<float>(1.0 - static_cast<double>(pull));
   int rc;
-  DPPF_SWITCH_M(p->M, {
+  DPPF_SWITCH_M(mg, {
     constexpr int kU = unroll_plain(kM) > 2 ? 2 : unroll_plain(kM);
-    auto k1 = k_seq1<kM, kU, REF>;
-    auto k2 = k_seq2<kM, kU, REF>;
     int grid = 0, gfull = 0;
-    if ((rc = grid_for(p, k1, 1, kBlocksPerCUReadOnly, &gfull, &grid))) return rc;
-    if ((rc = timing_begin(p, DPPF_K_SEQ_REDUCE, s))) return rc;
-    hipLaunchKernelGGL(k1, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, xc,
-                       pull, keep, p->partials, p->M);
-    if ((rc = timing_end(p, s))) return rc;
-    const int nparts = grid;
-    if ((rc = grid_for(p, k2, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
-    if ((rc = timing_begin(p, DPPF_K_SEQ_UPDATE, s))) return rc;
-    hipLaunchKernelGGL(k2, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, xc,
-                       pull, keep, push, p->partials, nparts, p->M, r_post_out);
-    if ((rc = timing_end(p, s))) return rc;
+    if (WRITE) {
+      auto kern = k_seq2<kM, kU, REF>;
+      if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, xc,
+                         rf, pull, keep, push, p->partials + m0, nparts, p->M,
+                         r_post_out ? r_post_out + m0 : nullptr);
+    } else {
+      auto kern = k_seq1<kM, kU, REF>;
+      if (shape->grid > 0) {     // later worker groups fill the same rows of the partial sums
+        gfull = shape->gfull;
+        grid = shape->grid;
+      } else {
+        if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadOnly, &gfull, &grid))) return rc;
+        shape->gfull = gfull;
+        shape->grid = grid;
+      }
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, xc,
+                         rf, pull, keep, p->partials + m0, p->M);
+    }
   })
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
+}
+
+template <int REF>
+int run_seq(dppf_plan* p, const void** xp, const void** xcp, const void** refp, float pull, float push,
+            float* r_post_out, hipStream_t s) {
+  GridShape shape;
+  int rc;
+  if ((rc = timing_begin(p, DPPF_K_SEQ_REDUCE, s))) return rc;
+  for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
+    const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
+    if ((rc = launch_seq<REF, false>(p, mg, m0, xp, xcp, refp, pull, push, 0, nullptr, &shape, s))) return rc;
+  }
+  if ((rc = timing_end(p, s))) return rc;
+  if ((rc = timing_begin(p, DPPF_K_SEQ_UPDATE, s))) return rc;
+  for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
+    const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
+    if ((rc = launch_seq<REF, true>(p, mg, m0, xp, xcp, refp, pull, push, shape.grid, r_post_out, nullptr, s)))
+      return rc;
+  }
+  return timing_end(p, s);
 }
 
 // The scratch average used when M > 8: a pointer table into the plan's own d-vector.
@@ -366,6 +396,13 @@ int scratch_xbar_table(dppf_plan* p, hipStream_t s, const void*** dev_out) {
   std::vector<const void*> host(static_cast<size_t>(p->T));
   for (int t = 0; t < p->T; ++t) host[t] = p->xbar_scratch + p->tensor_offset[t];
   return table_upload(p, dppf_plan::RXBAR_SCRATCH, host.data(), host.size(), s, dev_out);
+}
+
+// The second scratch vector (sum of unit gap vectors of the exact update), M > 8 only.
+int scratch_usum_table(dppf_plan* p, hipStream_t s, const void*** dev_out) {
+  std::vector<const void*> host(static_cast<size_t>(p->T));
+  for (int t = 0; t < p->T; ++t) host[t] = p->usum_scratch + p->tensor_offset[t];
+  return table_upload(p, dppf_plan::RUSUM_SCRATCH, host.data(), host.size(), s, dev_out);
 }
 
 // The tile list of a tensor list: every tensor cut into pieces of kTileElems elements, full
@@ -518,6 +555,7 @@ int dppf_plan_destroy(dppf_plan* p) {
   if (p->partials) (void)hipFree(p->partials);
   if (p->coef) (void)hipFree(p->coef);
   if (p->xbar_scratch) (void)hipFree(p->xbar_scratch);
+  if (p->usum_scratch) (void)hipFree(p->usum_scratch);
   for (auto& r : p->recs) {
     (void)hipEventDestroy(r.start);
     (void)hipEventDestroy(r.stop);
@@ -568,11 +606,14 @@ int dppf_plan_create(dppf_plan** out, int M, int T, const int64_t* numel) {
   PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->partials),
                      static_cast<size_t>(p->partials_rows) * M * sizeof(double)));
   PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->coef), static_cast<size_t>(M) * sizeof(Coef)));
-  if (M > kMaxTemplM && p->d > 0)
+  if (M > kMaxTemplM && p->d > 0) {
     PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->xbar_scratch), static_cast<size_t>(p->d) * sizeof(float)));
+    PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->usum_scratch), static_cast<size_t>(p->d) * sizeof(float)));
+  }
   const size_t n = static_cast<size_t>(M) * T;
   for (int r = 0; r < dppf_plan::NROLES; ++r) {
-    const bool per_model = (r == dppf_plan::RXBAR || r == dppf_plan::RXBAR_SCRATCH || r == dppf_plan::RXC);
+    const bool per_model = (r == dppf_plan::RXBAR || r == dppf_plan::RXBAR_SCRATCH ||
+                            r == dppf_plan::RUSUM_SCRATCH || r == dppf_plan::RXC);
     if (table_alloc(p->tab[r], per_model ? static_cast<size_t>(T) : n) != DPPF_OK) {
       dppf_plan_destroy(p);
       return DPPF_EHIP;
@@ -696,7 +737,6 @@ int dppf_round(dppf_plan* p, float* const* x, float* const* v, const float* cons
 int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float push_r, float* r_out,
                                float* c_out, void* stream) try {
   if (!p || !x) return DPPF_EINVAL;
-  if (p->M > kMaxTemplM) return DPPF_ELIMIT;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const void** xd = nullptr;
   int rc;
@@ -705,6 +745,44 @@ int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float 
     return rc;
   if (p->ntiles == 0) return launch_finalize(p, 0, pull, push_r / static_cast<float>(p->M), false, r_out, c_out, s);
   GridShape shape;
+  if (p->M > kMaxTemplM) {
+    // stored average -> distances per group -> coefficients and 1/r -> stored sum of unit gap
+    // vectors -> update per group
+    const float mf = static_cast<float>(p->M);
+    const void **avg = nullptr, **usum = nullptr;
+    if ((rc = scratch_xbar_table(p, s, &avg))) return rc;
+    if ((rc = scratch_usum_table(p, s, &usum))) return rc;
+    if ((rc = timing_begin(p, DPPF_K_MEAN, s))) return rc;
+    if ((rc = launch_mean_any(p, xd, avg, s))) return rc;
+    if ((rc = timing_end(p, s))) return rc;
+    if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
+    for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
+      const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
+      if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, kKeepNone, &shape, s)))
+        return rc;
+    }
+    if ((rc = timing_end(p, s))) return rc;
+    if ((rc = launch_finalize(p, shape.grid, pull, push_r / mf, true, r_out, c_out, s))) return rc;
+    if ((rc = timing_begin(p, DPPF_K_UPDATE_EXACT, s))) return rc;
+    int grid = 0, gfull = 0;
+    if ((rc = grid_for(p, k_unit_sum_any, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
+    hipLaunchKernelGGL(k_unit_sum_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M,
+                       p->T, (float* const*)(xd), (const float* const*)(avg), p->coef, (float* const*)(usum));
+    HIP_TRY(hipGetLastError());
+    for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
+      const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
+      float* const* xg = (float* const*)(xd) + static_cast<size_t>(m0) * p->T;
+      DPPF_SWITCH_M(mg, {
+        constexpr int kU = unroll_plain(kM) > 2 ? 2 : unroll_plain(kM);
+        auto kern = k_update_exact_given<kM, kU>;
+        if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, xg,
+                           (const float* const*)(avg), (const float* const*)(usum), p->coef + m0, push_r / (mf * mf));
+      })
+      HIP_TRY(hipGetLastError());
+    }
+    return timing_end(p, s);
+  }
   if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
   if ((rc = launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, kKeepTail, &shape, s))) return rc;
   if ((rc = timing_end(p, s))) return rc;
@@ -717,7 +795,6 @@ int dppf_pull_then_push(dppf_plan* p, float* const* x, const float* const* x_c, 
                         int push_from, float* r_post_out, void* stream) try {
   if (!p || !x || !x_c || (push_from != DPPF_PUSH_FROM_AVERAGE && push_from != DPPF_PUSH_FROM_CONSENSUS))
     return DPPF_EINVAL;
-  if (p->M > kMaxTemplM) return DPPF_ELIMIT;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const void **xd = nullptr, **xcd = nullptr;
   int rc;
@@ -728,8 +805,15 @@ int dppf_pull_then_push(dppf_plan* p, float* const* x, const float* const* x_c, 
                          static_cast<size_t>(p->T), s, &xcd)))
     return rc;
   if (p->ntiles == 0) return launch_finalize(p, 0, 0.f, 0.f, false, r_post_out, nullptr, s);
-  return push_from == DPPF_PUSH_FROM_AVERAGE ? launch_seq<0>(p, xd, xcd, pull, push, r_post_out, s)
-                                             : launch_seq<1>(p, xd, xcd, pull, push, r_post_out, s);
+  if (push_from == DPPF_PUSH_FROM_CONSENSUS) return run_seq<1>(p, xd, xcd, nullptr, pull, push, r_post_out, s);
+  if (p->M <= kMaxTemplM) return run_seq<0>(p, xd, xcd, nullptr, pull, push, r_post_out, s);
+  // more workers than one kernel sees at once: the pre-round average is stored first
+  const void** avg = nullptr;
+  if ((rc = scratch_xbar_table(p, s, &avg))) return rc;
+  if ((rc = timing_begin(p, DPPF_K_MEAN, s))) return rc;
+  if ((rc = launch_mean_any(p, xd, avg, s))) return rc;
+  if ((rc = timing_end(p, s))) return rc;
+  return run_seq<2>(p, xd, xcd, avg, pull, push, r_post_out, s);
 } DPPF_CATCH
 
 int dppf_local_adamw_step(dppf_plan* p, float* const* x, float* const* m1, float* const* m2,

@@ -34,6 +34,7 @@ struct Tile {
 struct Coef {
   float c;            // alpha - lambda / r_m
   int skip;           // r_m == 0: leave the worker untouched
+  float inv_r;        // 1 / r_m, 0 where r_m == 0
 };
 
 // ------------------------------------------------------------------------------- helpers
@@ -307,6 +308,7 @@ __global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ 
     if (coef) {
       coef[m].c = static_cast<float>(c);
       coef[m].skip = zero ? 1 : 0;
+      coef[m].inv_r = zero ? 0.f : static_cast<float>(1.0 / r);
     }
     if (r_out) r_out[m] = static_cast<float>(r);
     if (c_out) c_out[m] = static_cast<float>(c);
@@ -518,18 +520,97 @@ __global__ __launch_bounds__(kBlock) void k_update_exact(const Tile* __restrict_
   }
 }
 
+// ---- the exact update when there are more workers than fit in registers: the sum of unit gap
+// vectors S = sum_j (x_A - x_j) / r_j is materialised once (any M), then every group of up to 8
+// workers applies  x_m + (x_A - x_m) c_m + k2 S  with x_A and S read from memory.
+template <bool FULL>
+__device__ __forceinline__ void unit_sum_tile(const Tile tl, int M, int T, float* const* __restrict__ xp,
+                                              const float* xb, const Coef* __restrict__ coef, float* out) {
+#pragma unroll 1
+  for (int it = 0; it < kVecPerThread; ++it) {
+    const int e = 4 * (threadIdx.x + it * kBlock);
+    const int n = FULL ? 4 : tl.count - e;
+    const f4 xbar = load4<FULL>(xb + e, n);
+    f4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int m = 0; m < M; ++m)
+      s = fma4(xbar - load4<FULL>(xp[static_cast<size_t>(m) * T + tl.tensor] + tl.offset + e, n), coef[m].inv_r, s);
+    store4<FULL>(out + e, s, n);
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_unit_sum_any(const Tile* __restrict__ tiles, int nfull, int ntiles,
+                                                         int gfull, int M, int T, float* const* __restrict__ xp,
+                                                         const float* const* __restrict__ xbarp,
+                                                         const Coef* __restrict__ coef,
+                                                         float* const* __restrict__ sump) {
+  const TileWalk w = tile_walk(nfull, ntiles, gfull);
+  for (int t = w.first; t < w.end; t += w.stride) {
+    const Tile tl = tiles[t];
+    const float* xb = xbarp[tl.tensor] + tl.offset;
+    float* out = sump[tl.tensor] + tl.offset;
+    if (w.full) unit_sum_tile<true>(tl, M, T, xp, xb, coef, out);
+    else unit_sum_tile<false>(tl, M, T, xp, xb, coef, out);
+  }
+}
+
+template <int M, int U, bool FULL>
+__device__ __forceinline__ void exact_given_tile(const Tile tl, int T, float* const* __restrict__ xp,
+                                                 const float* xb, const float* us, const float (&c)[M], float k2) {
+#pragma unroll 1
+  for (int it = 0; it < kVecPerThread / U; ++it) {
+#pragma unroll
+    for (int k = 0; k < U; ++k) {
+      const int e = 4 * (threadIdx.x + (it * U + k) * kBlock);
+      const int n = FULL ? 4 : tl.count - e;
+      const f4 xbar = load4_stream<FULL>(xb + e, n);
+      const f4 usum = load4_stream<FULL>(us + e, n);
+#pragma unroll
+      for (int m = 0; m < M; ++m) {
+        float* x = xp[m * T + tl.tensor] + tl.offset + e;
+        const f4 xv = load4_stream<FULL>(x, n);
+        f4 moved = fma4(xbar - xv, c[m], xv);
+        moved = fma4(usum, k2, moved);
+        store4_stream<FULL>(x, moved, n);
+      }
+    }
+  }
+}
+
+template <int M, int U>
+__global__ __launch_bounds__(kBlock) void k_update_exact_given(const Tile* __restrict__ tiles, int nfull, int ntiles,
+                                                               int gfull, int T, float* const* __restrict__ xp,
+                                                               const float* const* __restrict__ xbarp,
+                                                               const float* const* __restrict__ sump,
+                                                               const Coef* __restrict__ coef, float k2) {
+  float c[M];
+#pragma unroll
+  for (int m = 0; m < M; ++m) c[m] = coef[m].c;
+  const TileWalk w = tile_walk(nfull, ntiles, gfull);
+  for (int t = w.first; t < w.end; t += w.stride) {
+    const Tile tl = tiles[t];
+    const float* xb = xbarp[tl.tensor] + tl.offset;
+    const float* us = sump[tl.tensor] + tl.offset;
+    if (w.full) exact_given_tile<M, U, true>(tl, T, xp, xb, us, c, k2);
+    else exact_given_tile<M, U, false>(tl, T, xp, xb, us, c, k2);
+  }
+}
+
 // ------------------------------------------- Alg. 1 written literally, any consensus variable
 // pulled_m = (1 - alpha) x_m + alpha x_C; gap_m = pulled_m - ref (ref = x_A before the round, or x_C);
 // r_m = ||gap_m||; x_m <- pulled_m + lambda gap_m / r_m  (no push where r_m = 0).
-// REF: 0 = push away from the average, 1 = push away from the consensus variable.
+// REF: 0 = push away from the average (formed from these M workers), 1 = push away from the
+// consensus variable, 2 = push away from an average that is read from memory (when the kernel
+// sees only a group of the workers).
 template <int M, int U, int REF, bool WRITE, bool FULL>
 __device__ __forceinline__ void seq_tile(const Tile tl, int T, float* const* __restrict__ xp,
-                                         const float* const* __restrict__ xcp, float pull, float keep,
+                                         const float* const* __restrict__ xcp,
+                                         const float* const* __restrict__ refp, float pull, float keep,
                                          const float (&scale)[M], float inv_m, double (&acc)[M]) {
   float* x[M];
 #pragma unroll
   for (int m = 0; m < M; ++m) x[m] = xp[m * T + tl.tensor] + tl.offset;
   const float* xc = xcp[tl.tensor] + tl.offset;
+  const float* rf = (REF == 2) ? refp[tl.tensor] + tl.offset : nullptr;
   float part[M];
 #pragma unroll
   for (int m = 0; m < M; ++m) part[m] = 0.f;
@@ -548,7 +629,9 @@ __device__ __forceinline__ void seq_tile(const Tile tl, int T, float* const* __r
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-      const f4 ref = (REF == 0) ? xv[k][0] + mean_offset<M>(xv[k], inv_m) : cv[k];
+      const f4 ref = (REF == 0)   ? xv[k][0] + mean_offset<M>(xv[k], inv_m)
+                     : (REF == 1) ? cv[k]
+                                  : load4<FULL>(rf + e[k], n[k]);
 #pragma unroll
       for (int m = 0; m < M; ++m) {
         const f4 pulled = fma4(cv[k], pull, xv[k][m] * keep);   // (1-alpha) x + alpha x_C: exactly x_C at alpha = 1
@@ -567,7 +650,8 @@ __device__ __forceinline__ void seq_tile(const Tile tl, int T, float* const* __r
 template <int M, int U, int REF>
 __global__ __launch_bounds__(kBlock) void k_seq1(const Tile* __restrict__ tiles, int nfull, int ntiles, int gfull,
                                                  int T, float* const* __restrict__ xp,
-                                                 const float* const* __restrict__ xcp, float pull, float keep,
+                                                 const float* const* __restrict__ xcp,
+                                                 const float* const* __restrict__ refp, float pull, float keep,
                                                  double* __restrict__ partials, int pstride) {
   double acc[M];
   float scale[M];
@@ -580,10 +664,10 @@ __global__ __launch_bounds__(kBlock) void k_seq1(const Tile* __restrict__ tiles,
   const TileWalk w = tile_walk(nfull, ntiles, gfull);
   if (w.full) {
     for (int t = w.first; t < w.end; t += w.stride)
-      seq_tile<M, U, REF, false, true>(tiles[t], T, xp, xcp, pull, keep, scale, inv_m, acc);
+      seq_tile<M, U, REF, false, true>(tiles[t], T, xp, xcp, refp, pull, keep, scale, inv_m, acc);
   } else {
     for (int t = w.first; t < w.end; t += w.stride)
-      seq_tile<M, U, REF, false, false>(tiles[t], T, xp, xcp, pull, keep, scale, inv_m, acc);
+      seq_tile<M, U, REF, false, false>(tiles[t], T, xp, xcp, refp, pull, keep, scale, inv_m, acc);
   }
   block_sums_store<M>(acc, partials + static_cast<size_t>(blockIdx.x) * pstride);
 }
@@ -591,7 +675,8 @@ __global__ __launch_bounds__(kBlock) void k_seq1(const Tile* __restrict__ tiles,
 template <int M, int U, int REF>
 __global__ __launch_bounds__(kBlock) void k_seq2(const Tile* __restrict__ tiles, int nfull, int ntiles, int gfull,
                                                  int T, float* const* __restrict__ xp,
-                                                 const float* const* __restrict__ xcp, float pull, float keep,
+                                                 const float* const* __restrict__ xcp,
+                                                 const float* const* __restrict__ refp, float pull, float keep,
                                                  float push, const double* __restrict__ partials, int nparts,
                                                  int pstride, float* __restrict__ r_post_out) {
   // lambda / r_m from the partial sums (c = 0 - push/r, so scale = -c; zero distance: no push)
@@ -607,10 +692,12 @@ __global__ __launch_bounds__(kBlock) void k_seq2(const Tile* __restrict__ tiles,
   const int last = (w.end - 1 - w.first) / w.stride;
   if (w.full) {
     for (int j = last; j >= 0; --j)
-      seq_tile<M, U, REF, true, true>(tiles[w.first + j * w.stride], T, xp, xcp, pull, keep, scale, inv_m, unused);
+      seq_tile<M, U, REF, true, true>(tiles[w.first + j * w.stride], T, xp, xcp, refp, pull, keep, scale, inv_m,
+                                      unused);
   } else {
     for (int j = last; j >= 0; --j)
-      seq_tile<M, U, REF, true, false>(tiles[w.first + j * w.stride], T, xp, xcp, pull, keep, scale, inv_m, unused);
+      seq_tile<M, U, REF, true, false>(tiles[w.first + j * w.stride], T, xp, xcp, refp, pull, keep, scale, inv_m,
+                                       unused);
   }
 }
 
