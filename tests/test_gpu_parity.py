@@ -524,3 +524,33 @@ def test_random_lists_with_mixed_alignment(case):
     assert_params_close(download_rows(x), ref_x, inp.offsets, 1, "x", c=ref_c)
     assert_params_close(download_rows(v), ref_v, inp.offsets, 1, "v")
     plan.close()
+
+
+def test_thousands_of_tiny_tensors():
+    # no full tile at all: 3000 tensors of 1..300 elements, every block walks partial tiles only
+    rng = np.random.default_rng(77)
+    sizes = [int(n) for n in rng.integers(1, 301, size=3000)]
+    spec = W.small_spec(M=4, seed=78, shapes=tuple((n,) for n in sizes))
+    h = _hyper(spec)
+    inp = W.make_inputs(spec)
+    gk = inp.grads(0)
+
+    def rows(arrays):          # carve the tensors out of one buffer per worker (allocation count stays small)
+        out = []
+        for a in arrays:
+            buf = torch.from_numpy(a).cuda()
+            out.append([buf[int(inp.offsets[t]):int(inp.offsets[t + 1])] for t in range(spec.T)])
+        return out
+
+    x, v, g = rows(inp.x), rows(inp.v), rows(gk)
+    r = torch.zeros(4, device="cuda")
+    c = torch.zeros(4, device="cuda")
+    plan = dppf.Plan(4, spec.numel)
+    plan.round(x, v, g, h["lr"], h["mu"], h["wd"], h["pull"], h["push"], r_out=r, c_out=c)
+    ref_x, ref_v, ref_r, ref_c, _ = O.dppf_round(np.stack(inp.x), np.stack(inp.v), np.stack(gk), h["lr"], h["mu"],
+                                                 h["wd"], h["pull"], h["push"])
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+    assert_rel(c.cpu().numpy(), ref_c, 1e-4, "c")
+    assert_params_close(download_rows(x), ref_x, inp.offsets, 1, "x")
+    assert_params_close(download_rows(v), ref_v, inp.offsets, 1, "v")
+    plan.close()
