@@ -130,7 +130,7 @@ int dppf_round(dppf_plan* plan, float* const* x, float* const* v, const float* c
  *   d_m = x_m - x_A;  x_m <- x_m - pull d_m + (push_r / M^2) (M d_m/||d_m|| - sum_j d_j/||d_j||).
  * push_r is the regulariser's own coefficient lambda_r (Eq. 5's lambda corresponds to push_r / M).
  * Workers at zero distance contribute a zero unit vector.  The average of the workers is
- * preserved.  r_out[m] = ||d_m||, c_out[m] = pull - (push_r/M)/r_m, both optional.  For M <= 8
+ * preserved.  r_out[m] = ||d_m||, c_out[m] = pull - (push_r/M)/r_m, both optional.  For M <= 16
  * the same two sweeps and the same memory traffic as dppf_pull_push_round; for more workers the
  * average and the sum of unit vectors are staged in two plan-owned d-vectors.  */
 int dppf_pull_push_round_exact(dppf_plan* plan, float* const* x, float pull, float push_r,

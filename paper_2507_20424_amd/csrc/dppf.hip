@@ -213,9 +213,12 @@ int keep_from_tile(const dppf_plan* p, int workers, KeepPolicy keep) {
   return tiles >= p->nfull ? 0 : p->nfull - static_cast<int>(tiles);
 }
 
-constexpr int unroll_plain(int M) { return M <= 4 ? 4 : (M <= 8 ? 2 : 1); }   // M*U <= 16 vectors
-constexpr int unroll_step_update(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }   // 2*M*U <= 16 vectors
-constexpr int unroll_fused(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }   // 3*M*U <= 24 vectors
+// 16-byte vectors a lane holds at once: M*U (plain), 2*M*U (update with the step), 3*M*U (fused).
+// Up to 8 workers the unroll keeps that at 16..24; 9..16 workers run without unrolling and still
+// fit the register file of a CU that holds one block (no spills).
+constexpr int unroll_plain(int M) { return M <= 4 ? 4 : (M <= 8 ? 2 : 1); }
+constexpr int unroll_step_update(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }
+constexpr int unroll_fused(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }
 
 #define DPPF_SWITCH_M(m_value, ...)                                \
   switch (m_value) {                                               \
@@ -227,10 +230,18 @@ constexpr int unroll_fused(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }   //
     case 6: { constexpr int kM = 6; __VA_ARGS__ } break;           \
     case 7: { constexpr int kM = 7; __VA_ARGS__ } break;           \
     case 8: { constexpr int kM = 8; __VA_ARGS__ } break;           \
+    case 9: { constexpr int kM = 9; __VA_ARGS__ } break;           \
+    case 10: { constexpr int kM = 10; __VA_ARGS__ } break;           \
+    case 11: { constexpr int kM = 11; __VA_ARGS__ } break;           \
+    case 12: { constexpr int kM = 12; __VA_ARGS__ } break;           \
+    case 13: { constexpr int kM = 13; __VA_ARGS__ } break;           \
+    case 14: { constexpr int kM = 14; __VA_ARGS__ } break;           \
+    case 15: { constexpr int kM = 15; __VA_ARGS__ } break;           \
+    case 16: { constexpr int kM = 16; __VA_ARGS__ } break;           \
     default: return DPPF_ELIMIT;                                   \
   }
 
-// Launch sweep 1 over workers [m0, m0+mg) of the table (mg <= 8).
+// Launch sweep 1 over workers [m0, m0+mg) of the table (mg <= kMaxTemplM).
 template <bool SGD, int XBAR, bool NORMS>
 int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const void** gp,
                   const void** xbarp, float lr, float mu, float wd, int m0, KeepPolicy keep, GridShape* shape,
@@ -309,7 +320,7 @@ int launch_local_step(dppf_plan* p, const void** xp, const void** vp, const void
 
 int launch_mean_any(dppf_plan* p, const void** xp, const void** xbarp, hipStream_t s) {
   int grid = 0, gfull = 0;
-  int rc = grid_for(p, k_mean_any, 1, kBlocksPerCUReadWrite, &gfull, &grid);
+  int rc = grid_for(p, k_mean_any, 1, kBlocksPerCUReadOnly, &gfull, &grid);
   if (rc) return rc;
   hipLaunchKernelGGL(k_mean_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M, p->T,
                      (float* const*)(xp), (float* const*)(xbarp));
@@ -391,14 +402,14 @@ int run_seq(dppf_plan* p, const void** xp, const void** xcp, const void** refp, 
   return timing_end(p, s);
 }
 
-// The scratch average used when M > 8: a pointer table into the plan's own d-vector.
+// The scratch average used when M > kMaxTemplM: a pointer table into the plan's own d-vector.
 int scratch_xbar_table(dppf_plan* p, hipStream_t s, const void*** dev_out) {
   std::vector<const void*> host(static_cast<size_t>(p->T));
   for (int t = 0; t < p->T; ++t) host[t] = p->xbar_scratch + p->tensor_offset[t];
   return table_upload(p, dppf_plan::RXBAR_SCRATCH, host.data(), host.size(), s, dev_out);
 }
 
-// The second scratch vector (sum of unit gap vectors of the exact update), M > 8 only.
+// The second scratch vector (sum of unit gap vectors of the exact update), M > kMaxTemplM only.
 int scratch_usum_table(dppf_plan* p, hipStream_t s, const void*** dev_out) {
   std::vector<const void*> host(static_cast<size_t>(p->T));
   for (int t = 0; t < p->T; ++t) host[t] = p->usum_scratch + p->tensor_offset[t];
@@ -500,8 +511,8 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
     if (rc) return rc;
     return timing_end(p, s);
   }
-  // M > 8: materialise the average once, then run the register-resident kernels over groups
-  // of up to 8 workers that read it back.
+  // More workers than the register-resident kernels take: materialise the average once, then run
+  // those kernels over groups of up to kMaxTemplM workers that read it back.
   if (with_step && (rc = launch_local_step(p, xd, vd, gd, lr, mu, wd, s))) return rc;
   const void** avg = xbd;
   if (!avg && (rc = scratch_xbar_table(p, s, &avg))) return rc;
@@ -765,7 +776,7 @@ int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float 
     if ((rc = launch_finalize(p, shape.grid, pull, push_r / mf, true, r_out, c_out, s))) return rc;
     if ((rc = timing_begin(p, DPPF_K_UPDATE_EXACT, s))) return rc;
     int grid = 0, gfull = 0;
-    if ((rc = grid_for(p, k_unit_sum_any, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
+    if ((rc = grid_for(p, k_unit_sum_any, 1, kBlocksPerCUReadOnly, &gfull, &grid))) return rc;
     hipLaunchKernelGGL(k_unit_sum_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M,
                        p->T, (float* const*)(xd), (const float* const*)(avg), p->coef, (float* const*)(usum));
     HIP_TRY(hipGetLastError());

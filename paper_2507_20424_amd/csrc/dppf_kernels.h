@@ -14,7 +14,8 @@ typedef f4 f4u __attribute__((aligned(4)));   // 16-byte vector that may sit on 
 constexpr int kBlock = 256;                   // threads per block (4 waves)
 constexpr int kTileElems = 4096;              // elements of ONE worker's tensor per tile (DPPF_TILE_ELEMS)
 constexpr int kVecPerThread = kTileElems / (4 * kBlock);   // 16-byte vectors per thread per tile
-constexpr int kMaxTemplM = 8;                 // worker counts with a register-resident kernel
+constexpr int kMaxTemplM = 16;                 // worker counts with a register-resident kernel
+constexpr int kAnyChunk = 4;                   // workers whose loads the any-M kernels keep in flight together
 constexpr int kMaxBlocksPerCU = 8;             // upper bound on resident blocks per CU (sizes buffers)
 // Resident blocks per CU by traffic pattern (measured): kernels that mix reads and writes run
 // fastest with ONE block per CU -- fewer concurrently open DRAM rows and longer same-direction
@@ -521,20 +522,45 @@ __global__ __launch_bounds__(kBlock) void k_update_exact(const Tile* __restrict_
 }
 
 // ---- the exact update when there are more workers than fit in registers: the sum of unit gap
-// vectors S = sum_j (x_A - x_j) / r_j is materialised once (any M), then every group of up to 8
-// workers applies  x_m + (x_A - x_m) c_m + k2 S  with x_A and S read from memory.
+// vectors S = sum_j (x_A - x_j) / r_j is materialised once (any M), then every group of up to
+// kMaxTemplM workers applies  x_m + (x_A - x_m) c_m + k2 S  with x_A and S read from memory.
 template <bool FULL>
 __device__ __forceinline__ void unit_sum_tile(const Tile tl, int M, int T, float* const* __restrict__ xp,
                                               const float* xb, const Coef* __restrict__ coef, float* out) {
-#pragma unroll 1
+  // Same chunked loads as the any-M average; the sum runs over the workers in ascending order.
+  f4 xbar[kVecPerThread], s[kVecPerThread];
+#pragma unroll
   for (int it = 0; it < kVecPerThread; ++it) {
     const int e = 4 * (threadIdx.x + it * kBlock);
-    const int n = FULL ? 4 : tl.count - e;
-    const f4 xbar = load4<FULL>(xb + e, n);
-    f4 s = {0.f, 0.f, 0.f, 0.f};
-    for (int m = 0; m < M; ++m)
-      s = fma4(xbar - load4<FULL>(xp[static_cast<size_t>(m) * T + tl.tensor] + tl.offset + e, n), coef[m].inv_r, s);
-    store4<FULL>(out + e, s, n);
+    xbar[it] = load4<FULL>(xb + e, FULL ? 4 : tl.count - e);
+    s[it] = (f4){0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll 1
+  for (int m = 0; m < M; m += kAnyChunk) {
+    f4 t[kAnyChunk][kVecPerThread];
+    float w[kAnyChunk];
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+        w[k] = coef[m + k].inv_r;
+#pragma unroll
+        for (int it = 0; it < kVecPerThread; ++it) {
+          const int e = 4 * (threadIdx.x + it * kBlock);
+          t[k][it] = load4<FULL>(base + e, FULL ? 4 : tl.count - e);
+        }
+      }
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+#pragma unroll
+        for (int it = 0; it < kVecPerThread; ++it) s[it] = fma4(xbar[it] - t[k][it], w[k], s[it]);
+      }
+  }
+#pragma unroll
+  for (int it = 0; it < kVecPerThread; ++it) {
+    const int e = 4 * (threadIdx.x + it * kBlock);
+    store4<FULL>(out + e, s[it], FULL ? 4 : tl.count - e);
   }
 }
 
@@ -919,18 +945,44 @@ __global__ __launch_bounds__(kBlock) void k_local_step(const Tile* __restrict__ 
   }
 }
 
-// ------------------------------------------- average over a runtime number of workers (M > 8)
+// ------------------------------- average over a runtime number of workers (M > kMaxTemplM)
 template <bool FULL>
 __device__ __forceinline__ void mean_any_tile(const Tile tl, int M, int T,
                                               float* const* __restrict__ xp, float* xb, float inv_m) {
-#pragma unroll 1
+  // Workers are taken kAnyChunk at a time and all of a chunk's loads are issued before the first
+  // is used; the sums still run over the workers in ascending order.
+  f4 x0[kVecPerThread], s[kVecPerThread];
+  const float* base0 = xp[tl.tensor] + tl.offset;
+#pragma unroll
   for (int it = 0; it < kVecPerThread; ++it) {
     const int e = 4 * (threadIdx.x + it * kBlock);
-    const int n = FULL ? 4 : tl.count - e;
-    const f4 x0 = load4<FULL>(xp[tl.tensor] + tl.offset + e, n);
-    f4 s = {0.f, 0.f, 0.f, 0.f};
-    for (int m = 1; m < M; ++m) s += load4<FULL>(xp[static_cast<size_t>(m) * T + tl.tensor] + tl.offset + e, n) - x0;
-    store4<FULL>(xb + e, x0 + scale_by_inverse_count(s, M, inv_m), n);
+    x0[it] = load4<FULL>(base0 + e, FULL ? 4 : tl.count - e);
+    s[it] = (f4){0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll 1
+  for (int m = 1; m < M; m += kAnyChunk) {
+    f4 t[kAnyChunk][kVecPerThread];
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+#pragma unroll
+        for (int it = 0; it < kVecPerThread; ++it) {
+          const int e = 4 * (threadIdx.x + it * kBlock);
+          t[k][it] = load4<FULL>(base + e, FULL ? 4 : tl.count - e);
+        }
+      }
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+#pragma unroll
+        for (int it = 0; it < kVecPerThread; ++it) s[it] += t[k][it] - x0[it];
+      }
+  }
+#pragma unroll
+  for (int it = 0; it < kVecPerThread; ++it) {
+    const int e = 4 * (threadIdx.x + it * kBlock);
+    store4<FULL>(xb + e, x0[it] + scale_by_inverse_count(s[it], M, inv_m), FULL ? 4 : tl.count - e);
   }
 }
 

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 from paper_2507_20424_amd import build as B, workloads as W  # noqa: E402
 
 
-@pytest.mark.parametrize("M", [2, 4, 9])
+@pytest.mark.parametrize("M", [2, 4, 9, 18])
 def test_fused_round_from_plain_c(M, tmp_path):
     if not os.path.exists(B.CLI):
         B.build_all(verbose=False)

@@ -23,7 +23,7 @@ def _hyper(spec):
                 push=f32(spec.push))
 
 
-WORKER_COUNTS = [1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 16]
+WORKER_COUNTS = [1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 16, 17, 33]
 
 
 @pytest.mark.parametrize("M", WORKER_COUNTS)
@@ -66,7 +66,7 @@ def test_round_small_lists(M, misalign):
     plan.close()
 
 
-@pytest.mark.parametrize("M", [2, 4, 8, 9])
+@pytest.mark.parametrize("M", [2, 4, 8, 9, 16, 19])
 @pytest.mark.parametrize("wd", [0.0, 1e-3])
 def test_local_step_and_fused_round(M, wd):
     spec = W.small_spec(M=M, seed=200 + M, tau=3, weight_decay=wd)
@@ -127,7 +127,7 @@ def test_fused_equals_step_then_round_bitwise():
     plan.close()
 
 
-@pytest.mark.parametrize("M", [2, 3, 4, 7, 8, 12])
+@pytest.mark.parametrize("M", [2, 3, 4, 7, 8, 12, 21])
 def test_identical_replicas_do_not_move(M):
     # zero distance: no direction, no displacement, r = 0, c = alpha, no NaN/Inf -- bit for bit,
     # negative zeros included
@@ -450,9 +450,9 @@ def test_measurement_utilities():
     assert torch.all(buf[stride:stride + length] == 1.0) and torch.all(buf[stride + length:2 * stride] == 0)
 
 
-@pytest.mark.parametrize("M", [12, 17])
+@pytest.mark.parametrize("M", [12, 17, 35])
 def test_many_workers_on_a_list_that_fills_the_chip(M):
-    # M > 8 goes through a stored average and groups of up to 8 workers; here with more tiles than
+    # M > 16 goes through a stored average and groups of up to 16 workers; here with more tiles than
     # compute units, so the groups' launches must share one layout of the partial sums
     spec = W.small_spec(M=M, seed=900 + M, shapes=((1_300_000,), (777,), (1_200_003,), (5,)))
     h = _hyper(spec)

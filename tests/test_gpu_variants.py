@@ -17,7 +17,7 @@ def _rows(inp, arrays, misalign=0):
     return [upload_tensors(a, inp.offsets, misalign) for a in arrays]
 
 
-@pytest.mark.parametrize("M", [2, 3, 4, 5, 8, 9, 12, 17])
+@pytest.mark.parametrize("M", [2, 3, 4, 5, 8, 9, 12, 17, 34])
 def test_exact_two_term_round(M):
     spec = W.small_spec(M=M, seed=300 + M)
     inp = W.make_inputs(spec)
@@ -63,7 +63,7 @@ def test_exact_round_zero_distance_worker():
     plan.close()
 
 
-@pytest.mark.parametrize("M", [2, 4, 7, 8, 9, 11, 16])
+@pytest.mark.parametrize("M", [2, 4, 7, 8, 9, 11, 16, 17, 36])
 @pytest.mark.parametrize("push_from", ["average", "consensus"])
 def test_pull_then_push_with_supplied_consensus(M, push_from):
     spec = W.small_spec(M=M, seed=400 + M)
@@ -135,7 +135,7 @@ def test_adamw_local_step(M):
     plan.close()
 
 
-@pytest.mark.parametrize("M", [2, 4, 8, 9])
+@pytest.mark.parametrize("M", [2, 4, 8, 9, 16, 18])
 def test_fused_adamw_round(M):
     # the ViT runs of the paper: AdamW local steps, then the pull-push round
     spec = W.small_spec(M=M, seed=520 + M)
