@@ -69,7 +69,8 @@ int dppf_last_hip_error(void);
 typedef struct dppf_plan dppf_plan;
 
 /* numel: HOST array of T element counts.  Uses the HIP device that is current at the time of the
- * call; the same device must be current whenever the plan is used.  */
+ * call; the same device must be current whenever the plan is used (a call made with another
+ * device current returns DPPF_EINVAL and enqueues nothing).  */
 int dppf_plan_create(dppf_plan** out, int M, int T, const int64_t* numel);
 int dppf_plan_destroy(dppf_plan* plan);
 /* d = sum of numel. */

@@ -100,6 +100,10 @@ namespace {
 int table_upload(dppf_plan* p, int role, const void* const* host, size_t n, hipStream_t s,
                  const void*** dev_out) {
   PtrTable& t = p->tab[role];
+  // Every entry point that takes a plan comes through here first: its buffers live on one device.
+  int current = -1;
+  HIP_TRY(hipGetDevice(&current));
+  if (current != p->device) return DPPF_EINVAL;
   if (n == 0) {
     *dev_out = t.dev;   // never dereferenced: no tiles
     return DPPF_OK;
@@ -706,7 +710,9 @@ int dppf_dist_norms(dppf_plan* p, const float* const* x, const float* const* xba
     const void** avg = xbd;
     if (!avg) {
       if ((rc = scratch_xbar_table(p, s, &avg))) return rc;
+      if ((rc = timing_begin(p, DPPF_K_MEAN, s))) return rc;
       if ((rc = launch_mean_any(p, xd, avg, s))) return rc;
+      if ((rc = timing_end(p, s))) return rc;
     }
     if ((rc = timing_begin(p, DPPF_K_REDUCE, s))) return rc;
     for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
@@ -1012,12 +1018,17 @@ int dppf_plan_timing_enable(dppf_plan* p, int enable) {
 
 int dppf_plan_timing_read(dppf_plan* p, int* kernel_id, float* ms, int cap) try {
   if (!p || cap < 0 || (cap > 0 && (!kernel_id || !ms))) return DPPF_EINVAL;
-  int n = 0;
+  // A bracket whose launch failed half way has no recorded stop event: such a record is dropped.
+  // Every record leaves the list whatever happens, so no event is ever handed out twice.
+  int n = 0, failed = 0;
   for (auto& r : p->recs) {
-    HIP_TRY(hipEventSynchronize(r.stop));
-    if (n < cap) {
-      float t = 0.f;
-      HIP_TRY(hipEventElapsedTime(&t, r.start, r.stop));
+    float t = 0.f;
+    hipError_t e = hipEventSynchronize(r.stop);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
+    if (e != hipSuccess) {
+      g_last_hip_error = static_cast<int>(e);
+      ++failed;
+    } else if (n < cap) {
       kernel_id[n] = r.id;
       ms[n] = t;
       ++n;
@@ -1026,6 +1037,7 @@ int dppf_plan_timing_read(dppf_plan* p, int* kernel_id, float* ms, int cap) try 
     p->event_pool.push_back(r.stop);
   }
   p->recs.clear();
+  if (failed) (void)hipGetLastError();   // the unreadable records are gone; leave no sticky error behind
   return n;
 } DPPF_CATCH
 
