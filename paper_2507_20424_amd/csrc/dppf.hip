@@ -12,12 +12,17 @@
 //     the stepped x: sweep 1 reads x, v, g and writes only v; sweep 2 reads the OLD x and the NEW
 //     v, rebuilds x - lr v with the same fused multiply-add (same bits) and applies Eq. 5.
 //     28 bytes instead of 32, and 20 of them reads (reads stream faster than writes here).
-//   * a tensor list is cut into tiles of kTileElems consecutive elements of one tensor; thread
-//     blocks walk the tile list with a grid stride, so one launch covers any number of tensors
-//     of any size.  Full tiles and partial ones (tensor tails, small tensors) are walked by
-//     different blocks.  Loads are 16-byte vectors with 4-byte alignment (legal for global
-//     memory on gfx9), so no tensor needs 16-byte alignment; only the last, partial vector of a
-//     tensor is handled element by element.
+//   * a tensor list is cut into tiles of kTileElems consecutive elements of one tensor; a fixed
+//     number of thread blocks (one or two per CU) walks the tile list, so one launch covers any
+//     number of tensors of any size.  Full tiles and partial ones (tensor tails, small tensors)
+//     are walked by different blocks.  Loads are 16-byte vectors with 4-byte alignment (legal for
+//     global memory on gfx9), so no tensor needs 16-byte alignment; only the last, partial vector
+//     of a tensor is handled element by element.
+//   * the chip's compute dies do not stream at the same rate, so an even split of the tiles leaves
+//     the faster ones idle at the end: the read-write sweeps split only the first part of their
+//     tiles evenly and hand the rest out on demand from a counter (see walk_items).  Partial sums
+//     are kept per block for the even part and per tile for the on-demand part, so the result does
+//     not depend on which block took which tile.
 //   * the gap of a worker to the average is formed relative to worker 0 (see mean_offset), so it
 //     keeps full relative precision and is exactly zero for identical replicas.
 //   * squared distances: fp32 inside a tile (16 values per lane), fp64 across tiles, lanes,
@@ -79,8 +84,9 @@ struct dppf_plan {
   int ntiles = 0;
   int nfull = 0;                // tiles [0, nfull) are full, [nfull, ntiles) partial
   Tile* tiles_dev = nullptr;
-  double* partials = nullptr;   // [max blocks][M]
+  double* partials = nullptr;   // [partials_rows][M]: one row per block, then one per on-demand tile
   int partials_rows = 0;
+  Sched* sched = nullptr;       // the counter behind the on-demand part of a kernel's tile walk
   Coef* coef = nullptr;         // [M]
   float* xbar_scratch = nullptr;            // d floats, only when M > kMaxTemplM
   float* usum_scratch = nullptr;            // d floats, only when M > kMaxTemplM (exact update)
@@ -193,12 +199,46 @@ int grid_for(dppf_plan* p, K kernel, int per_tile_items, int want_per_cu, int* g
   const long long part_items = static_cast<long long>(p->ntiles - p->nfull) * per_tile_items;
   if (gpart > part_items) gpart = part_items;
   *gfull_out = static_cast<int>(gfull);
-  *grid_out = static_cast<int>(gfull + gpart);   // <= num_cu * kMaxBlocksPerCU = partials_rows
+  *grid_out = static_cast<int>(gfull + gpart);   // <= num_cu * kMaxBlocksPerCU
   return DPPF_OK;
 }
 
+// How much of a kernel's full-tile work is handed out on demand instead of being split evenly
+// (see walk_items).  Measured on the ViT-B-sized list: kernels that store nothing per item gain
+// most with half of the work on demand (sweep 2: -5 %); the fused reducing sweeps pay a block-wide
+// sum and a row of partial sums per on-demand tile and do best with a third (-2 %); the pure-read
+// reducing sweeps (a few microseconds per tile) lose more to that than they gain, so they keep the
+// even split.
+enum OnDemand { kOnDemandNone = 0, kOnDemandThird = 3, kOnDemandHalf = 2 };
+constexpr int kMinRoundsOnDemand = 4;   // fewer items per block than this: not worth a counter
+
+// Items [0, returned value) of `count` are split evenly over `blocks` blocks, the rest handed out
+// on demand; returns count when nothing is.
+long long evenly_split_items(long long count, int blocks, OnDemand share) {
+  if (share == kOnDemandNone || blocks <= 0) return count;
+  const long long rounds = count / blocks;
+  if (rounds < kMinRoundsOnDemand) return count;
+  const long long on_demand_rounds = (rounds + share - 1) / share;
+  return (rounds - on_demand_rounds) * blocks;
+}
+
+Walk make_walk(const dppf_plan* p, int gfull, int per_tile_items, OnDemand share) {
+  Walk w;
+  w.nfull = p->nfull;
+  w.ntiles = p->ntiles;
+  w.gfull = gfull;
+  const long long count = static_cast<long long>(p->nfull) * per_tile_items;
+  w.nstatic = static_cast<int>(evenly_split_items(count, gfull, share));
+  w.sched = w.nstatic < count ? p->sched : nullptr;
+  return w;
+}
+
+// The launch shape of a reducing sweep: later launches that add to the same rows of partial
+// sums (worker groups) and the launch that reads them must agree on it.
 struct GridShape {
-  int gfull = 0, grid = 0;
+  int grid = 0;
+  Walk walk{};
+  int nparts() const { return grid + (walk.nfull - walk.nstatic); }   // reducing sweeps have one item per tile
 };
 
 // Which of sweep 1's x loads go through the caches (see k_sweep1).
@@ -257,20 +297,23 @@ int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const 
   DPPF_SWITCH_M(mg, {
     constexpr int kU = SGD ? unroll_fused(kM) : unroll_plain(kM);
     auto kern = k_sweep1<kM, kU, SGD, XBAR, NORMS>;
-    int grid = 0, gfull = 0;
+    int grid = 0;
+    Walk walk;
     if (shape && shape->grid > 0) {   // later worker groups must fill the same rows of the partial sums
-      gfull = shape->gfull;
       grid = shape->grid;
+      walk = shape->walk;
     } else {
+      int gfull = 0;
       int rc = grid_for(p, kern, 1, (SGD || XBAR == 1) ? kBlocksPerCUReadWrite : kBlocksPerCUReadOnly, &gfull,
                         &grid);
       if (rc) return rc;
+      walk = make_walk(p, gfull, 1, SGD ? kOnDemandThird : kOnDemandNone);
       if (shape) {
-        shape->gfull = gfull;
         shape->grid = grid;
+        shape->walk = walk;
       }
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, v, g, xb,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, walk, p->T, x, v, g, xb,
                        lr, mu, wd, p->partials + m0, p->M, keep_from_tile(p, mg, keep));
   })
   HIP_TRY(hipGetLastError());
@@ -289,7 +332,7 @@ int launch_sweep2(dppf_plan* p, int mg, const void** xp, const void** vp, const 
     int grid = 0, gfull = 0;
     int rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid);
     if (rc) return rc;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, v, xb, lr,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandHalf), p->T, x, v, xb, lr,
                        p->coef + m0, 1.0f / static_cast<float>(kM), p->partials, nparts, p->M, pull, push,
                        r_out, c_out);
   })
@@ -315,9 +358,8 @@ int launch_local_step(dppf_plan* p, const void** xp, const void** vp, const void
   if (rc) return rc;
   rc = timing_begin(p, DPPF_K_LOCAL_STEP, s);
   if (rc) return rc;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M, p->T,
-                     (float* const*)(xp), (float* const*)(vp),
-                     (const float* const*)(gp), lr, mu, wd);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, p->M, kOnDemandHalf), p->M,
+                     p->T, (float* const*)(xp), (float* const*)(vp), (const float* const*)(gp), lr, mu, wd);
   HIP_TRY(hipGetLastError());
   return timing_end(p, s);
 }
@@ -326,8 +368,8 @@ int launch_mean_any(dppf_plan* p, const void** xp, const void** xbarp, hipStream
   int grid = 0, gfull = 0;
   int rc = grid_for(p, k_mean_any, 1, kBlocksPerCUReadOnly, &gfull, &grid);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_mean_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M, p->T,
-                     (float* const*)(xp), (float* const*)(xbarp));
+  hipLaunchKernelGGL(k_mean_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandNone),
+                     p->M, p->T, (float* const*)(xp), (float* const*)(xbarp));
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
 }
@@ -342,7 +384,7 @@ int launch_update_exact(dppf_plan* p, const void** xp, int nparts, float pull, f
     int grid = 0, gfull = 0;
     int rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid);
     if (rc) return rc;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandHalf), p->T, x,
                        p->partials, nparts, p->M, pull, push_r / mf, push_r / (mf * mf), r_out, c_out);
   })
   HIP_TRY(hipGetLastError());
@@ -365,20 +407,17 @@ int launch_seq(dppf_plan* p, int mg, int m0, const void** xp, const void** xcp, 
     if (WRITE) {
       auto kern = k_seq2<kM, kU, REF>;
       if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
-      hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, xc,
-                         rf, pull, keep, push, p->partials + m0, nparts, p->M,
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandHalf), p->T, x,
+                         xc, rf, pull, keep, push, p->partials + m0, nparts, p->M,
                          r_post_out ? r_post_out + m0 : nullptr);
     } else {
       auto kern = k_seq1<kM, kU, REF>;
-      if (shape->grid > 0) {     // later worker groups fill the same rows of the partial sums
-        gfull = shape->gfull;
-        grid = shape->grid;
-      } else {
+      if (shape->grid == 0) {     // later worker groups fill the same rows of the partial sums
         if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadOnly, &gfull, &grid))) return rc;
-        shape->gfull = gfull;
         shape->grid = grid;
+        shape->walk = make_walk(p, gfull, 1, kOnDemandNone);
       }
-      hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, x, xc,
+      hipLaunchKernelGGL(kern, dim3(shape->grid), dim3(kBlock), 0, s, p->tiles_dev, shape->walk, p->T, x, xc,
                          rf, pull, keep, p->partials + m0, p->M);
     }
   })
@@ -400,7 +439,7 @@ int run_seq(dppf_plan* p, const void** xp, const void** xcp, const void** refp, 
   if ((rc = timing_begin(p, DPPF_K_SEQ_UPDATE, s))) return rc;
   for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
     const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
-    if ((rc = launch_seq<REF, true>(p, mg, m0, xp, xcp, refp, pull, push, shape.grid, r_post_out, nullptr, s)))
+    if ((rc = launch_seq<REF, true>(p, mg, m0, xp, xcp, refp, pull, push, shape.nparts(), r_post_out, nullptr, s)))
       return rc;
   }
   return timing_end(p, s);
@@ -467,8 +506,8 @@ int launch_adamw_step(dppf_plan* p, const void** xd, const void** ad, const void
   int grid = 0, gfull = 0, rc;
   if ((rc = grid_for(p, kern, p->M, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
   if ((rc = timing_begin(p, DPPF_K_ADAMW_STEP, s))) return rc;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M, p->T,
-                     (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), hp);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, p->M, kOnDemandHalf), p->M,
+                     p->T, (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), hp);
   HIP_TRY(hipGetLastError());
   return timing_end(p, s);
 }
@@ -509,9 +548,9 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
     if ((rc = timing_end(p, s))) return rc;
     if ((rc = timing_begin(p, with_step ? DPPF_K_STEP_UPDATE : DPPF_K_UPDATE, s))) return rc;
     if (with_step)
-      rc = launch_sweep2<0, true, true>(p, p->M, xd, vd, nullptr, lr, 0, shape.grid, pull, push, r_out, c_out, s);
+      rc = launch_sweep2<0, true, true>(p, p->M, xd, vd, nullptr, lr, 0, shape.nparts(), pull, push, r_out, c_out, s);
     else
-      rc = launch_sweep2<0, false, true>(p, p->M, xd, nullptr, nullptr, 0.f, 0, shape.grid, pull, push, r_out, c_out, s);
+      rc = launch_sweep2<0, false, true>(p, p->M, xd, nullptr, nullptr, 0.f, 0, shape.nparts(), pull, push, r_out, c_out, s);
     if (rc) return rc;
     return timing_end(p, s);
   }
@@ -529,7 +568,7 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
     if ((rc = launch_sweep1<false, 2, true>(p, mg, xd, nullptr, nullptr, avg, 0, 0, 0, m0, kKeepNone, &shape, s))) return rc;
   }
   if ((rc = timing_end(p, s))) return rc;
-  if ((rc = launch_finalize(p, shape.grid, pull, push, true, r_out, c_out, s))) return rc;
+  if ((rc = launch_finalize(p, shape.nparts(), pull, push, true, r_out, c_out, s))) return rc;
   if ((rc = timing_begin(p, DPPF_K_UPDATE, s))) return rc;
   for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
     const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
@@ -569,6 +608,7 @@ int dppf_plan_destroy(dppf_plan* p) {
   if (p->tiles_dev) (void)hipFree(p->tiles_dev);
   if (p->partials) (void)hipFree(p->partials);
   if (p->coef) (void)hipFree(p->coef);
+  if (p->sched) (void)hipFree(p->sched);
   if (p->xbar_scratch) (void)hipFree(p->xbar_scratch);
   if (p->usum_scratch) (void)hipFree(p->usum_scratch);
   for (auto& r : p->recs) {
@@ -614,13 +654,15 @@ int dppf_plan_create(dppf_plan** out, int M, int T, const int64_t* numel) {
   hipDeviceProp_t prop;
   PLAN_TRY(hipGetDeviceProperties(&prop, p->device));
   p->num_cu = prop.multiProcessorCount;
-  p->partials_rows = p->num_cu * kMaxBlocksPerCU;
+  p->partials_rows = p->num_cu * kMaxBlocksPerCU + p->nfull;   // one per block + at most one per full tile
   PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->tiles_dev), (tiles.size() + 1) * sizeof(Tile)));
   if (!tiles.empty())
     PLAN_TRY(hipMemcpy(p->tiles_dev, tiles.data(), tiles.size() * sizeof(Tile), hipMemcpyHostToDevice));
   PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->partials),
                      static_cast<size_t>(p->partials_rows) * M * sizeof(double)));
   PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->coef), static_cast<size_t>(M) * sizeof(Coef)));
+  PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->sched), sizeof(Sched)));
+  PLAN_TRY(hipMemset(p->sched, 0, sizeof(Sched)));
   if (M > kMaxTemplM && p->d > 0) {
     PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->xbar_scratch), static_cast<size_t>(p->d) * sizeof(float)));
     PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->usum_scratch), static_cast<size_t>(p->d) * sizeof(float)));
@@ -721,7 +763,7 @@ int dppf_dist_norms(dppf_plan* p, const float* const* x, const float* const* xba
     }
     if ((rc = timing_end(p, s))) return rc;
   }
-  return launch_finalize(p, shape.grid, 0.f, 0.f, false, r_out, nullptr, s);
+  return launch_finalize(p, shape.nparts(), 0.f, 0.f, false, r_out, nullptr, s);
 } DPPF_CATCH
 
 int dppf_pull_push_round(dppf_plan* p, float* const* x, float pull, float push, float* r_out,
@@ -779,12 +821,12 @@ int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float 
         return rc;
     }
     if ((rc = timing_end(p, s))) return rc;
-    if ((rc = launch_finalize(p, shape.grid, pull, push_r / mf, true, r_out, c_out, s))) return rc;
+    if ((rc = launch_finalize(p, shape.nparts(), pull, push_r / mf, true, r_out, c_out, s))) return rc;
     if ((rc = timing_begin(p, DPPF_K_UPDATE_EXACT, s))) return rc;
     int grid = 0, gfull = 0;
     if ((rc = grid_for(p, k_unit_sum_any, 1, kBlocksPerCUReadOnly, &gfull, &grid))) return rc;
-    hipLaunchKernelGGL(k_unit_sum_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->M,
-                       p->T, (float* const*)(xd), (const float* const*)(avg), p->coef, (float* const*)(usum));
+    hipLaunchKernelGGL(k_unit_sum_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandNone),
+                       p->M, p->T, (float* const*)(xd), (const float* const*)(avg), p->coef, (float* const*)(usum));
     HIP_TRY(hipGetLastError());
     for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
       const int mg = (p->M - m0 < kMaxTemplM) ? p->M - m0 : kMaxTemplM;
@@ -793,7 +835,7 @@ int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float 
         constexpr int kU = unroll_plain(kM) > 2 ? 2 : unroll_plain(kM);
         auto kern = k_update_exact_given<kM, kU>;
         if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T, xg,
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandHalf), p->T, xg,
                            (const float* const*)(avg), (const float* const*)(usum), p->coef + m0, push_r / (mf * mf));
       })
       HIP_TRY(hipGetLastError());
@@ -804,7 +846,7 @@ int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float 
   if ((rc = launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, kKeepTail, &shape, s))) return rc;
   if ((rc = timing_end(p, s))) return rc;
   if ((rc = timing_begin(p, DPPF_K_UPDATE_EXACT, s))) return rc;
-  if ((rc = launch_update_exact(p, xd, shape.grid, pull, push_r, r_out, c_out, s))) return rc;
+  if ((rc = launch_update_exact(p, xd, shape.nparts(), pull, push_r, r_out, c_out, s))) return rc;
   return timing_end(p, s);
 } DPPF_CATCH
 
@@ -868,20 +910,23 @@ int dppf_round_adamw(dppf_plan* p, float* const* x, float* const* m1, float* con
     if ((rc = launch_adamw_step(p, xd, ad, sd, gd, hp, s))) return rc;
     return round_impl(p, false, x, nullptr, nullptr, 0.f, 0.f, 0.f, pull, push, r_out, c_out, nullptr, s);
   }
-  int grid = 0, gfull = 0;
+  GridShape shape;
   if ((rc = timing_begin(p, DPPF_K_ADAMW_REDUCE, s))) return rc;
   DPPF_SWITCH_M(p->M, {
     constexpr int kU = kM <= 2 ? 2 : 1;     // 4*M*U <= 32 vectors in flight
     auto kern = k_adamw_reduce<kM, kU>;
-    if ((rc = grid_for(p, kern, 1, kBlocksPerCUHeavyMath, &gfull, &grid))) return rc;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, p->nfull, p->ntiles, gfull, p->T,
+    int gfull = 0;
+    if ((rc = grid_for(p, kern, 1, kBlocksPerCUHeavyMath, &gfull, &shape.grid))) return rc;
+    shape.walk = make_walk(p, gfull, 1, kOnDemandThird);
+    hipLaunchKernelGGL(kern, dim3(shape.grid), dim3(kBlock), 0, s, p->tiles_dev, shape.walk, p->T,
                        (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), hp,
                        p->partials, p->M);
   })
   HIP_TRY(hipGetLastError());
   if ((rc = timing_end(p, s))) return rc;
   if ((rc = timing_begin(p, DPPF_K_UPDATE, s))) return rc;
-  if ((rc = launch_sweep2<0, false, true>(p, p->M, xd, nullptr, nullptr, 0.f, 0, grid, pull, push, r_out, c_out, s)))
+  if ((rc = launch_sweep2<0, false, true>(p, p->M, xd, nullptr, nullptr, 0.f, 0, shape.nparts(), pull, push, r_out,
+                                          c_out, s)))
     return rc;
   return timing_end(p, s);
 } DPPF_CATCH
@@ -973,19 +1018,30 @@ int dppf_util_copy(float* dst, const float* src, int64_t n, void* stream) {
 
 // ---- streaming probe (measurement aid)
 int dppf_util_stream_probe(float* base, int64_t stride, int64_t n, int reads, int writes, int inplace,
-                           int blocks_per_cu, void* stream) {
+                           int blocks_per_cu, int on_demand, void* stream) {
   if (!base || n < 0 || stride < n || blocks_per_cu < 1 || blocks_per_cu > 16) return DPPF_EINVAL;
   if (reinterpret_cast<uintptr_t>(base) & 15u || (stride & 3)) return DPPF_EINVAL;
+  if (n / 1024 >= INT32_MAX) return DPPF_ELIMIT;
   int dev = 0, cus = 0;
   HIP_TRY(hipGetDevice(&dev));
   HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  Sched* sched = nullptr;   // this device's copy of the probe's counter
+  HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&sched), HIP_SYMBOL(g_probe_sched)));
   const dim3 grid(static_cast<unsigned>(cus * blocks_per_cu)), block(kBlock);
   hipStream_t s = static_cast<hipStream_t>(stream);
   float* sink = base;   // never written unless a sum hits one magic value
 #define DPPF_PROBE(R_, W_, U_, IP_)                                                              \
   if (reads == R_ && writes == W_ && (inplace != 0) == IP_) {                                    \
+    const long long tiles_ = n / (static_cast<long long>(kBlock) * U_ * 4);                      \
+    const long long items_ = (tiles_ + kProbeItemTiles - 1) / kProbeItemTiles;                   \
+    Walk walk_;                                                                                  \
+    walk_.nfull = walk_.ntiles = static_cast<int>(items_);                                       \
+    walk_.gfull = static_cast<int>(grid.x);                                                      \
+    walk_.nstatic = static_cast<int>(                                                            \
+        evenly_split_items(items_, walk_.gfull, on_demand ? kOnDemandHalf : kOnDemandNone));     \
+    walk_.sched = walk_.nstatic < items_ ? sched : nullptr;                                      \
     hipLaunchKernelGGL((k_probe<R_, W_, U_, IP_>), grid, block, 0, s, base, static_cast<long long>(stride), \
-                       static_cast<long long>(n), sink);                                         \
+                       static_cast<long long>(n), sink, walk_);                                  \
     HIP_TRY(hipGetLastError());                                                                  \
     return DPPF_OK;                                                                              \
   }

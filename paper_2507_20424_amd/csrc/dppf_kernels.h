@@ -5,6 +5,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 namespace {
 
 
@@ -39,33 +41,42 @@ struct Coef {
 };
 
 // ------------------------------------------------------------------------------- helpers
+// Tensor data always live in device (global) memory.  The pointers come out of pointer tables, so
+// the compiler cannot know that and would use flat addressing; these types tell it.
+typedef __attribute__((address_space(1))) const f4u* gvec_in;
+typedef __attribute__((address_space(1))) f4u* gvec_out;
+typedef __attribute__((address_space(1))) const float* gf_in;
+typedef __attribute__((address_space(1))) float* gf_out;
+
 template <bool FULL>
 __device__ __forceinline__ f4 load4(const float* p, int n) {
-  if (FULL || n >= 4) return *reinterpret_cast<const f4u*>(p);
+  if (FULL || n >= 4) return *(gvec_in)(p);
+  gf_in q = (gf_in)(p);
   f4 r = {0.f, 0.f, 0.f, 0.f};
-  if (n > 0) r.x = p[0];
-  if (n > 1) r.y = p[1];
-  if (n > 2) r.z = p[2];
+  if (n > 0) r.x = q[0];
+  if (n > 1) r.y = q[1];
+  if (n > 2) r.z = q[2];
   return r;
 }
 
 template <bool FULL>
 __device__ __forceinline__ f4 load4_stream(const float* p, int n) {   // data not needed again soon
-  if (FULL || n >= 4) return __builtin_nontemporal_load(reinterpret_cast<const f4u*>(p));
+  if (FULL || n >= 4) return __builtin_nontemporal_load((gvec_in)(p));
   return load4<false>(p, n);
 }
 
 template <bool FULL>
 __device__ __forceinline__ void store4(float* p, f4 v, int n) {
-  if (FULL || n >= 4) { *reinterpret_cast<f4u*>(p) = v; return; }
-  if (n > 0) p[0] = v.x;
-  if (n > 1) p[1] = v.y;
-  if (n > 2) p[2] = v.z;
+  if (FULL || n >= 4) { *(gvec_out)(p) = v; return; }
+  gf_out q = (gf_out)(p);
+  if (n > 0) q[0] = v.x;
+  if (n > 1) q[1] = v.y;
+  if (n > 2) q[2] = v.z;
 }
 
 template <bool FULL>
 __device__ __forceinline__ void store4_stream(float* p, f4 v, int n) {
-  if (FULL || n >= 4) { __builtin_nontemporal_store(v, reinterpret_cast<f4u*>(p)); return; }
+  if (FULL || n >= 4) { __builtin_nontemporal_store(v, (gvec_out)(p)); return; }
   store4<false>(p, v, n);
 }
 
@@ -119,15 +130,18 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-// Block-wide sums of M per-lane doubles; thread m < M writes the m-th sum to out[m].
+// Block-wide sums of M per-lane doubles; thread m < M writes the m-th sum to out[m].  The per-lane
+// values are set back to zero.  May be called repeatedly by a block, with at least one barrier
+// between two calls (the loop of walk_items has them).
 template <int M>
-__device__ __forceinline__ void block_sums_store(const double (&acc)[M], double* out) {
+__device__ __forceinline__ void block_sums_flush(double (&acc)[M], double* out) {
   __shared__ double lds[kBlock / 64][M];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
   for (int m = 0; m < M; ++m) {
     double s = wave_sum(acc[m]);
     if (lane == 0) lds[wave][m] = s;
+    acc[m] = 0.0;
   }
   __syncthreads();
   if (threadIdx.x < M) {
@@ -139,28 +153,94 @@ __device__ __forceinline__ void block_sums_store(const double (&acc)[M], double*
 }
 
 // The tile list holds all full tiles first, then the partial ones (tensor tails and tensors
-// smaller than a tile).  Blocks [0, gfull) walk the full tiles with a stride of gfull; the
-// remaining blocks walk the partial tiles.  A list of many small tensors therefore does not put
-// short, latency-bound tiles into the streaming blocks' loops.
-struct TileWalk {
-  int first, end, stride;
-  bool full;
+// smaller than a tile).  Blocks [0, gfull) take the full tiles, the remaining blocks the partial
+// ones, so a list of many small tensors does not put short, latency-bound tiles into the streaming
+// blocks' loops.
+//
+// Full tiles are work ITEMS (one per tile, or one per (tile, worker) pair).  Items [0, nstatic) go
+// to the blocks with a fixed stride; items [nstatic, count) are handed out on demand from a counter
+// in device memory.  The compute dies of the chip do not stream at the same rate (blocks on some
+// finish a fixed share about 10 % earlier than on others), and with a fixed split the early ones
+// idle while the late ones finish; handing out the tail on demand keeps every CU busy to the end.
+// The counter resets itself: the last block to leave puts it back to zero, so every launch finds
+// it clean and nothing has to be cleared between launches (also inside a captured graph).
+struct Sched {
+  unsigned int next;   // next on-demand item to hand out
+  unsigned int done;   // full-tile blocks that have left the kernel
 };
 
-__device__ __forceinline__ TileWalk tile_walk(int nfull, int ntiles, int gfull) {
-  TileWalk w;
-  if (static_cast<int>(blockIdx.x) < gfull) {
-    w.first = blockIdx.x;
-    w.end = nfull;
-    w.stride = gfull;
-    w.full = true;
-  } else {
-    w.first = nfull + static_cast<int>(blockIdx.x) - gfull;
-    w.end = ntiles;
-    w.stride = static_cast<int>(gridDim.x) - gfull;
-    w.full = false;
+struct Walk {
+  int nfull, ntiles;   // tiles [0, nfull) are full, [nfull, ntiles) partial
+  int gfull;           // blocks [0, gfull) take full tiles
+  int nstatic;         // full-tile items with a fixed owner; the rest are handed out on demand
+  Sched* sched;        // used only when nstatic < number of full-tile items
+};
+
+using FullTile = std::integral_constant<bool, true>;
+using PartialTile = std::integral_constant<bool, false>;
+
+// Calls body(item, FullTile{} or PartialTile{}) for every item of this block, all threads of the
+// block together.  item counts within the full tiles or within the partial tiles.  A block owns
+// the items congruent to its index (modulo the number of blocks on that part of the list) in the
+// forward and in the REVERSE walk alike, so on a small model sweep 2 finds in its die's L2 what
+// sweep 1 left there.  REVERSE walks from the far end: the fixed shares are the upper items and the
+// on-demand ones run down to item 0, so sweep 2 starts where sweep 1 stopped, whose data are still
+// in the last-level cache.  flush(row) is called with row = blockIdx.x once the block's fixed share
+// (or its partial tiles) is done, and with row = gridDim.x + k after the k-th on-demand item:
+// kernels that reduce store their partial sums there, so that the set of rows and what each row
+// holds never depend on which block took which item -- results stay bit-reproducible.
+template <bool REVERSE, typename Body, typename Flush>
+__device__ __forceinline__ void walk_items(const Walk& w, int per_tile, Body&& body, Flush&& flush) {
+  __shared__ int s_next;
+  const bool full = static_cast<int>(blockIdx.x) < w.gfull;
+  const int me = full ? static_cast<int>(blockIdx.x) : static_cast<int>(blockIdx.x) - w.gfull;
+  const int lanes = full ? w.gfull : static_cast<int>(gridDim.x) - w.gfull;
+  const int count = (full ? w.nfull : w.ntiles - w.nfull) * per_tile;
+  // last item this block owns (below `me` if it owns none)
+  const int last_owned = count > me ? me + ((count - 1 - me) / lanes) * lanes : me - lanes;
+  if (!full) {
+    if (REVERSE) {
+      for (int j = last_owned; j >= me; j -= lanes) body(j, PartialTile{});
+    } else {
+      for (int j = me; j < count; j += lanes) body(j, PartialTile{});
+    }
+    flush(static_cast<int>(blockIdx.x));
+    return;
   }
-  return w;
+  const int ndyn = count - w.nstatic;            // items handed out on demand
+  const int lo = REVERSE ? ndyn : 0;             // fixed shares are the items [lo, lo + nstatic)
+  // The first on-demand item is requested right away: the answer is there long before it is needed.
+  unsigned int fetched = 0;
+  if (ndyn > 0 && threadIdx.x == 0) fetched = atomicAdd(&w.sched->next, 1u);
+  int j = REVERSE ? last_owned : me;
+  bool on_demand = false;
+  for (;;) {
+    if (!on_demand && (REVERSE ? j < lo : j >= lo + w.nstatic)) {
+      flush(static_cast<int>(blockIdx.x));
+      if (ndyn <= 0) break;
+      on_demand = true;
+    }
+    int k = 0;
+    if (on_demand) {
+      if (threadIdx.x == 0) s_next = static_cast<int>(fetched);
+      __syncthreads();
+      k = s_next;
+      __syncthreads();
+      if (k >= ndyn) break;            // every block gets here: the counter only grows
+      if (threadIdx.x == 0) fetched = atomicAdd(&w.sched->next, 1u);   // the one after, while this one runs
+      j = REVERSE ? ndyn - 1 - k : w.nstatic + k;
+    }
+    body(j, FullTile{});
+    if (on_demand) flush(static_cast<int>(gridDim.x) + k);
+    else j += REVERSE ? -lanes : lanes;
+  }
+  // A block counts itself out only after its last request has been answered, so when the count is
+  // complete nobody will touch the counter again in this launch.
+  if (ndyn > 0 && threadIdx.x == 0 &&
+      atomicAdd(&w.sched->done, 1u) == static_cast<unsigned int>(w.gfull) - 1u) {
+    atomicExch(&w.sched->next, 0u);
+    atomicExch(&w.sched->done, 0u);
+  }
 }
 
 // --------------------------------------------------------------------- sweep 1 of the round
@@ -255,8 +335,7 @@ __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* 
 }
 
 template <int M, int U, bool SGD, int XBAR, bool NORMS>
-__global__ __launch_bounds__(kBlock) void k_sweep1(const Tile* __restrict__ tiles, int nfull, int ntiles,
-                                                   int gfull, int T,
+__global__ __launch_bounds__(kBlock) void k_sweep1(const Tile* __restrict__ tiles, const Walk w, int T,
                                                    float* const* __restrict__ xp,
                                                    float* const* __restrict__ vp,
                                                    const float* const* __restrict__ gp,
@@ -267,21 +346,30 @@ __global__ __launch_bounds__(kBlock) void k_sweep1(const Tile* __restrict__ tile
 #pragma unroll
   for (int m = 0; m < M; ++m) acc[m] = 0.0;
   const float inv_m = 1.0f / static_cast<float>(M);
-  const TileWalk w = tile_walk(nfull, ntiles, gfull);
-  if (w.full) {
-    // Pure reads stream fastest when they bypass the last-level cache, but the tiles this sweep
-    // touches last are the ones sweep 2 (which walks backwards) reads first: those, from
-    // keep_from on, go through the cache so that sweep 2 finds them there.
-    int t = w.first;
-    for (; t < w.end && t < keep_from; t += w.stride)
-      sweep1_tile<M, U, SGD, XBAR, NORMS, true, false>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
-    for (; t < w.end; t += w.stride)
-      sweep1_tile<M, U, SGD, XBAR, NORMS, true, true>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
-  } else {
-    for (int t = w.first; t < w.end; t += w.stride)
-      sweep1_tile<M, U, SGD, XBAR, NORMS, false, true>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
-  }
-  if (NORMS) block_sums_store<M>(acc, partials + static_cast<size_t>(blockIdx.x) * pstride);
+  walk_items<false>(
+      w, 1,
+      [&](int t, auto full) {
+        if constexpr (decltype(full)::value) {
+          // Pure reads stream fastest when they bypass the last-level cache, but the tiles this sweep
+          // touches last are the ones sweep 2 (which walks backwards) reads first: those, from
+          // keep_from on, go through the cache so that sweep 2 finds them there.
+          if (t < keep_from) {
+            sweep1_tile<M, U, SGD, XBAR, NORMS, true, false>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
+          } else {
+            // The two branches differ only in the cache hint of their loads; left alone the compiler
+            // merges them and drops the hint.  The empty statements keep them apart.
+            asm volatile("" ::: "memory");
+            sweep1_tile<M, U, SGD, XBAR, NORMS, true, true>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
+            asm volatile("" ::: "memory");
+          }
+        } else {
+          sweep1_tile<M, U, SGD, XBAR, NORMS, false, true>(tiles[w.nfull + t], T, xp, vp, gp, xbarp, lr, mu, wd,
+                                                           inv_m, acc);
+        }
+      },
+      [&](int row) {
+        if (NORMS) block_sums_flush<M>(acc, partials + static_cast<size_t>(row) * pstride);
+      });
 }
 
 // ------------------------------------------------------- partial sums -> r_m and c_m (Eq. 5)
@@ -426,8 +514,7 @@ __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* 
 // FOLD: the coefficients are derived here from sweep 1's partial sums (no finalize launch);
 // otherwise they are read from `coef`.
 template <int M, int U, int XBAR, bool STEP, bool FOLD>
-__global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tiles, int nfull, int ntiles,
-                                                   int gfull, int T,
+__global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tiles, const Walk w, int T,
                                                    float* const* __restrict__ xp,
                                                    const float* const* __restrict__ vp,
                                                    const float* const* __restrict__ xbarp, float lr,
@@ -447,19 +534,15 @@ __global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tile
       skip[m] = coef[m].skip != 0;
     }
   }
-  const TileWalk w = tile_walk(nfull, ntiles, gfull);
-  if (w.first >= w.end) return;
-  // opposite walk order to sweep 1
-  const int last = (w.end - 1 - w.first) / w.stride;
-  if (w.full) {
-    for (int j = last; j >= 0; --j)
-      sweep2_tile<M, U, XBAR, STEP, true>(tiles[w.first + j * w.stride], T, xp, vp, xbarp, lr, c, skip,
-                                          inv_m_total);
-  } else {
-    for (int j = last; j >= 0; --j)
-      sweep2_tile<M, U, XBAR, STEP, false>(tiles[w.first + j * w.stride], T, xp, vp, xbarp, lr, c, skip,
-                                           inv_m_total);
-  }
+  walk_items<true>(
+      w, 1,
+      [&](int t, auto full) {
+        if constexpr (decltype(full)::value)
+          sweep2_tile<M, U, XBAR, STEP, true>(tiles[t], T, xp, vp, xbarp, lr, c, skip, inv_m_total);
+        else
+          sweep2_tile<M, U, XBAR, STEP, false>(tiles[w.nfull + t], T, xp, vp, xbarp, lr, c, skip, inv_m_total);
+      },
+      [](int) {});
 }
 
 // ------------------------------------------------ sweep 2 with the exact two-term gradient
@@ -502,8 +585,8 @@ __device__ __forceinline__ void exact_tile(const Tile tl, int T, float* const* _
 }
 
 template <int M, int U>
-__global__ __launch_bounds__(kBlock) void k_update_exact(const Tile* __restrict__ tiles, int nfull, int ntiles,
-                                                         int gfull, int T, float* const* __restrict__ xp,
+__global__ __launch_bounds__(kBlock) void k_update_exact(const Tile* __restrict__ tiles, const Walk w, int T,
+                                                         float* const* __restrict__ xp,
                                                          const double* __restrict__ partials, int nparts,
                                                          int pstride, float pull, float push_over_m, float k2,
                                                          float* __restrict__ r_out, float* __restrict__ c_out) {
@@ -511,14 +594,13 @@ __global__ __launch_bounds__(kBlock) void k_update_exact(const Tile* __restrict_
   bool skip[M];
   coefficients_from_partials<M>(partials, nparts, pstride, pull, push_over_m, c, skip, inv_r, r_out, c_out);
   const float inv_m = 1.0f / static_cast<float>(M);
-  const TileWalk w = tile_walk(nfull, ntiles, gfull);
-  if (w.first >= w.end) return;
-  const int last = (w.end - 1 - w.first) / w.stride;
-  if (w.full) {
-    for (int j = last; j >= 0; --j) exact_tile<M, U, true>(tiles[w.first + j * w.stride], T, xp, c, inv_r, k2, inv_m);
-  } else {
-    for (int j = last; j >= 0; --j) exact_tile<M, U, false>(tiles[w.first + j * w.stride], T, xp, c, inv_r, k2, inv_m);
-  }
+  walk_items<true>(
+      w, 1,
+      [&](int t, auto full) {
+        if constexpr (decltype(full)::value) exact_tile<M, U, true>(tiles[t], T, xp, c, inv_r, k2, inv_m);
+        else exact_tile<M, U, false>(tiles[w.nfull + t], T, xp, c, inv_r, k2, inv_m);
+      },
+      [](int) {});
 }
 
 // ---- the exact update when there are more workers than fit in registers: the sum of unit gap
@@ -564,19 +646,19 @@ __device__ __forceinline__ void unit_sum_tile(const Tile tl, int M, int T, float
   }
 }
 
-__global__ __launch_bounds__(kBlock) void k_unit_sum_any(const Tile* __restrict__ tiles, int nfull, int ntiles,
-                                                         int gfull, int M, int T, float* const* __restrict__ xp,
+__global__ __launch_bounds__(kBlock) void k_unit_sum_any(const Tile* __restrict__ tiles, const Walk w, int M, int T,
+                                                         float* const* __restrict__ xp,
                                                          const float* const* __restrict__ xbarp,
                                                          const Coef* __restrict__ coef,
                                                          float* const* __restrict__ sump) {
-  const TileWalk w = tile_walk(nfull, ntiles, gfull);
-  for (int t = w.first; t < w.end; t += w.stride) {
-    const Tile tl = tiles[t];
-    const float* xb = xbarp[tl.tensor] + tl.offset;
-    float* out = sump[tl.tensor] + tl.offset;
-    if (w.full) unit_sum_tile<true>(tl, M, T, xp, xb, coef, out);
-    else unit_sum_tile<false>(tl, M, T, xp, xb, coef, out);
-  }
+  walk_items<false>(
+      w, 1,
+      [&](int t, auto full) {
+        constexpr bool kFull = decltype(full)::value;
+        const Tile tl = tiles[kFull ? t : w.nfull + t];
+        unit_sum_tile<kFull>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset, coef, sump[tl.tensor] + tl.offset);
+      },
+      [](int) {});
 }
 
 template <int M, int U, bool FULL>
@@ -603,22 +685,22 @@ __device__ __forceinline__ void exact_given_tile(const Tile tl, int T, float* co
 }
 
 template <int M, int U>
-__global__ __launch_bounds__(kBlock) void k_update_exact_given(const Tile* __restrict__ tiles, int nfull, int ntiles,
-                                                               int gfull, int T, float* const* __restrict__ xp,
+__global__ __launch_bounds__(kBlock) void k_update_exact_given(const Tile* __restrict__ tiles, const Walk w, int T,
+                                                               float* const* __restrict__ xp,
                                                                const float* const* __restrict__ xbarp,
                                                                const float* const* __restrict__ sump,
                                                                const Coef* __restrict__ coef, float k2) {
   float c[M];
 #pragma unroll
   for (int m = 0; m < M; ++m) c[m] = coef[m].c;
-  const TileWalk w = tile_walk(nfull, ntiles, gfull);
-  for (int t = w.first; t < w.end; t += w.stride) {
-    const Tile tl = tiles[t];
-    const float* xb = xbarp[tl.tensor] + tl.offset;
-    const float* us = sump[tl.tensor] + tl.offset;
-    if (w.full) exact_given_tile<M, U, true>(tl, T, xp, xb, us, c, k2);
-    else exact_given_tile<M, U, false>(tl, T, xp, xb, us, c, k2);
-  }
+  walk_items<false>(
+      w, 1,
+      [&](int t, auto full) {
+        constexpr bool kFull = decltype(full)::value;
+        const Tile tl = tiles[kFull ? t : w.nfull + t];
+        exact_given_tile<M, U, kFull>(tl, T, xp, xbarp[tl.tensor] + tl.offset, sump[tl.tensor] + tl.offset, c, k2);
+      },
+      [](int) {});
 }
 
 // ------------------------------------------- Alg. 1 written literally, any consensus variable
@@ -674,8 +756,8 @@ __device__ __forceinline__ void seq_tile(const Tile tl, int T, float* const* __r
 }
 
 template <int M, int U, int REF>
-__global__ __launch_bounds__(kBlock) void k_seq1(const Tile* __restrict__ tiles, int nfull, int ntiles, int gfull,
-                                                 int T, float* const* __restrict__ xp,
+__global__ __launch_bounds__(kBlock) void k_seq1(const Tile* __restrict__ tiles, const Walk w, int T,
+                                                 float* const* __restrict__ xp,
                                                  const float* const* __restrict__ xcp,
                                                  const float* const* __restrict__ refp, float pull, float keep,
                                                  double* __restrict__ partials, int pstride) {
@@ -687,20 +769,19 @@ __global__ __launch_bounds__(kBlock) void k_seq1(const Tile* __restrict__ tiles,
     scale[m] = 0.f;
   }
   const float inv_m = 1.0f / static_cast<float>(M);
-  const TileWalk w = tile_walk(nfull, ntiles, gfull);
-  if (w.full) {
-    for (int t = w.first; t < w.end; t += w.stride)
-      seq_tile<M, U, REF, false, true>(tiles[t], T, xp, xcp, refp, pull, keep, scale, inv_m, acc);
-  } else {
-    for (int t = w.first; t < w.end; t += w.stride)
-      seq_tile<M, U, REF, false, false>(tiles[t], T, xp, xcp, refp, pull, keep, scale, inv_m, acc);
-  }
-  block_sums_store<M>(acc, partials + static_cast<size_t>(blockIdx.x) * pstride);
+  walk_items<false>(
+      w, 1,
+      [&](int t, auto full) {
+        constexpr bool kFull = decltype(full)::value;
+        seq_tile<M, U, REF, false, kFull>(tiles[kFull ? t : w.nfull + t], T, xp, xcp, refp, pull, keep, scale, inv_m,
+                                          acc);
+      },
+      [&](int row) { block_sums_flush<M>(acc, partials + static_cast<size_t>(row) * pstride); });
 }
 
 template <int M, int U, int REF>
-__global__ __launch_bounds__(kBlock) void k_seq2(const Tile* __restrict__ tiles, int nfull, int ntiles, int gfull,
-                                                 int T, float* const* __restrict__ xp,
+__global__ __launch_bounds__(kBlock) void k_seq2(const Tile* __restrict__ tiles, const Walk w, int T,
+                                                 float* const* __restrict__ xp,
                                                  const float* const* __restrict__ xcp,
                                                  const float* const* __restrict__ refp, float pull, float keep,
                                                  float push, const double* __restrict__ partials, int nparts,
@@ -713,18 +794,14 @@ __global__ __launch_bounds__(kBlock) void k_seq2(const Tile* __restrict__ tiles,
   for (int m = 0; m < M; ++m) scale[m] = skip[m] ? 0.f : -c[m];
   double unused[M];
   const float inv_m = 1.0f / static_cast<float>(M);
-  const TileWalk w = tile_walk(nfull, ntiles, gfull);
-  if (w.first >= w.end) return;
-  const int last = (w.end - 1 - w.first) / w.stride;
-  if (w.full) {
-    for (int j = last; j >= 0; --j)
-      seq_tile<M, U, REF, true, true>(tiles[w.first + j * w.stride], T, xp, xcp, refp, pull, keep, scale, inv_m,
-                                      unused);
-  } else {
-    for (int j = last; j >= 0; --j)
-      seq_tile<M, U, REF, true, false>(tiles[w.first + j * w.stride], T, xp, xcp, refp, pull, keep, scale, inv_m,
-                                       unused);
-  }
+  walk_items<true>(
+      w, 1,
+      [&](int t, auto full) {
+        constexpr bool kFull = decltype(full)::value;
+        seq_tile<M, U, REF, true, kFull>(tiles[kFull ? t : w.nfull + t], T, xp, xcp, refp, pull, keep, scale, inv_m,
+                                         unused);
+      },
+      [](int) {});
 }
 
 // ------------------------------------------------------------------ AdamW local step
@@ -783,26 +860,23 @@ __device__ __forceinline__ void adamw_tile(float* x, float* m1, float* m2, const
 }
 
 template <int U>
-__global__ __launch_bounds__(kBlock) void k_adamw_step(const Tile* __restrict__ tiles, int nfull, int ntiles,
-                                                       int gfull, int M, int T, float* const* __restrict__ xp,
+__global__ __launch_bounds__(kBlock) void k_adamw_step(const Tile* __restrict__ tiles, const Walk w, int M, int T,
+                                                       float* const* __restrict__ xp,
                                                        float* const* __restrict__ ap, float* const* __restrict__ sp,
                                                        const float* const* __restrict__ gp, const AdamHyper hp) {
-  const bool full = static_cast<int>(blockIdx.x) < gfull;
-  const long long base = full ? 0 : nfull;
-  const long long count = full ? nfull : ntiles - nfull;
-  const long long first = full ? blockIdx.x : static_cast<long long>(blockIdx.x) - gfull;
-  const long long stride = full ? gfull : static_cast<long long>(gridDim.x) - gfull;
-  for (long long j = first; j < count * M; j += stride) {
-    const int m = static_cast<int>(j / count);
-    const Tile tl = tiles[base + (j - static_cast<long long>(m) * count)];
-    const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
-    float* x = xp[slot] + tl.offset;
-    float* a = ap[slot] + tl.offset;
-    float* q = sp[slot] + tl.offset;
-    const float* g = gp[slot] + tl.offset;
-    if (full) adamw_tile<U, true>(x, a, q, g, tl.count, hp);
-    else adamw_tile<U, false>(x, a, q, g, tl.count, hp);
-  }
+  // work items are (tile, worker) pairs, worker-major
+  walk_items<false>(
+      w, M,
+      [&](int item, auto full) {
+        constexpr bool kFull = decltype(full)::value;
+        const int per_worker = kFull ? w.nfull : w.ntiles - w.nfull;
+        const int m = item / per_worker;
+        const Tile tl = tiles[(kFull ? 0 : w.nfull) + (item - m * per_worker)];
+        const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
+        adamw_tile<U, kFull>(xp[slot] + tl.offset, ap[slot] + tl.offset, sp[slot] + tl.offset, gp[slot] + tl.offset,
+                             tl.count, hp);
+      },
+      [](int) {});
 }
 
 // Sweep 1 of the round with the AdamW step folded in: read x, m1, m2, g of all M workers, step,
@@ -856,8 +930,8 @@ __device__ __forceinline__ void adamw_reduce_tile(const Tile tl, int T, float* c
 }
 
 template <int M, int U>
-__global__ __launch_bounds__(kBlock) void k_adamw_reduce(const Tile* __restrict__ tiles, int nfull, int ntiles,
-                                                         int gfull, int T, float* const* __restrict__ xp,
+__global__ __launch_bounds__(kBlock) void k_adamw_reduce(const Tile* __restrict__ tiles, const Walk w, int T,
+                                                         float* const* __restrict__ xp,
                                                          float* const* __restrict__ ap,
                                                          float* const* __restrict__ sp,
                                                          const float* const* __restrict__ gp, const AdamHyper hp,
@@ -866,15 +940,13 @@ __global__ __launch_bounds__(kBlock) void k_adamw_reduce(const Tile* __restrict_
 #pragma unroll
   for (int m = 0; m < M; ++m) acc[m] = 0.0;
   const float inv_m = 1.0f / static_cast<float>(M);
-  const TileWalk w = tile_walk(nfull, ntiles, gfull);
-  if (w.full) {
-    for (int t = w.first; t < w.end; t += w.stride)
-      adamw_reduce_tile<M, U, true>(tiles[t], T, xp, ap, sp, gp, hp, inv_m, acc);
-  } else {
-    for (int t = w.first; t < w.end; t += w.stride)
-      adamw_reduce_tile<M, U, false>(tiles[t], T, xp, ap, sp, gp, hp, inv_m, acc);
-  }
-  block_sums_store<M>(acc, partials + static_cast<size_t>(blockIdx.x) * pstride);
+  walk_items<false>(
+      w, 1,
+      [&](int t, auto full) {
+        constexpr bool kFull = decltype(full)::value;
+        adamw_reduce_tile<M, U, kFull>(tiles[kFull ? t : w.nfull + t], T, xp, ap, sp, gp, hp, inv_m, acc);
+      },
+      [&](int row) { block_sums_flush<M>(acc, partials + static_cast<size_t>(row) * pstride); });
 }
 
 // ------------------------------------------------ by-products the paper logs every round
@@ -919,30 +991,23 @@ __device__ __forceinline__ void local_tile(float* x, float* v, const float* g, i
 }
 
 template <int U>
-__global__ __launch_bounds__(kBlock) void k_local_step(const Tile* __restrict__ tiles, int nfull, int ntiles,
-                                                       int gfull, int M, int T,
+__global__ __launch_bounds__(kBlock) void k_local_step(const Tile* __restrict__ tiles, const Walk w, int M, int T,
                                                        float* const* __restrict__ xp,
                                                        float* const* __restrict__ vp,
                                                        const float* const* __restrict__ gp, float lr,
                                                        float mu, float wd) {
-  // work items are (tile, worker) pairs; blocks [0, gfull) take the full tiles
-  const bool full = static_cast<int>(blockIdx.x) < gfull;
-  const long long base = full ? 0 : nfull;
-  const long long count = full ? nfull : ntiles - nfull;
-  const long long first = full ? blockIdx.x : static_cast<long long>(blockIdx.x) - gfull;
-  const long long stride = full ? gfull : static_cast<long long>(gridDim.x) - gfull;
-  for (long long j = first; j < count * M; j += stride) {
-    const int m = static_cast<int>(j / count);
-    const Tile tl = tiles[base + (j - static_cast<long long>(m) * count)];
-    const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
-    float* x = xp[slot] + tl.offset;
-    float* v = vp[slot] + tl.offset;
-    const float* g = gp[slot] + tl.offset;
-    if (full)
-      local_tile<U, true>(x, v, g, tl.count, lr, mu, wd);
-    else
-      local_tile<U, false>(x, v, g, tl.count, lr, mu, wd);
-  }
+  // work items are (tile, worker) pairs, worker-major
+  walk_items<false>(
+      w, M,
+      [&](int item, auto full) {
+        constexpr bool kFull = decltype(full)::value;
+        const int per_worker = kFull ? w.nfull : w.ntiles - w.nfull;
+        const int m = item / per_worker;
+        const Tile tl = tiles[(kFull ? 0 : w.nfull) + (item - m * per_worker)];
+        const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
+        local_tile<U, kFull>(xp[slot] + tl.offset, vp[slot] + tl.offset, gp[slot] + tl.offset, tl.count, lr, mu, wd);
+      },
+      [](int) {});
 }
 
 // ------------------------------- average over a runtime number of workers (M > kMaxTemplM)
@@ -986,18 +1051,18 @@ __device__ __forceinline__ void mean_any_tile(const Tile tl, int M, int T,
   }
 }
 
-__global__ __launch_bounds__(kBlock) void k_mean_any(const Tile* __restrict__ tiles, int nfull, int ntiles,
-                                                     int gfull, int M, int T,
+__global__ __launch_bounds__(kBlock) void k_mean_any(const Tile* __restrict__ tiles, const Walk w, int M, int T,
                                                      float* const* __restrict__ xp,
                                                      float* const* __restrict__ xbarp) {
   const float inv_m = 1.0f / static_cast<float>(M);
-  const TileWalk w = tile_walk(nfull, ntiles, gfull);
-  for (int t = w.first; t < w.end; t += w.stride) {
-    const Tile tl = tiles[t];
-    float* xb = xbarp[tl.tensor] + tl.offset;
-    if (w.full) mean_any_tile<true>(tl, M, T, xp, xb, inv_m);
-    else mean_any_tile<false>(tl, M, T, xp, xb, inv_m);
-  }
+  walk_items<false>(
+      w, 1,
+      [&](int t, auto full) {
+        constexpr bool kFull = decltype(full)::value;
+        const Tile tl = tiles[kFull ? t : w.nfull + t];
+        mean_any_tile<kFull>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset, inv_m);
+      },
+      [](int) {});
 }
 
 // ---------------------------------------------- plain copy (bandwidth / counter calibration)
@@ -1014,42 +1079,55 @@ __global__ __launch_bounds__(kBlock) void k_copy(float* __restrict__ dst, const 
 // Stream k is the n floats at base + k*stride.  Each element's R values are added and the sum
 // (times w+1) is stored to W streams: streams R..R+W-1, or, with INPLACE, streams 0..W-1 (read
 // and written by the same lane).  Gives the device's practical bandwidth for a given read/write
-// mix, the ceiling the DPPF kernels are compared with.
+// mix, the ceiling the DPPF kernels are compared with.  The blocks walk items of kProbeItemTiles
+// tiles the way the DPPF kernels walk their tiles (walk_items): an even split, or an even split
+// with the tail handed out on demand.
+constexpr int kProbeItemTiles = 16;
+__device__ Sched g_probe_sched;
+
 template <int R, int W, int U, bool INPLACE>
 __global__ __launch_bounds__(kBlock) void k_probe(float* __restrict__ base, long long stride, long long n,
-                                                  float* __restrict__ sink) {
+                                                  float* __restrict__ sink, const Walk walk) {
   const long long tile = static_cast<long long>(kBlock) * U * 4;
   const long long ntiles = n / tile;
   f4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (long long t = blockIdx.x; t < ntiles; t += gridDim.x) {
-    f4 v[U];
+  walk_items<false>(
+      walk, 1,
+      [&](int item, auto) {
+        const long long t0 = static_cast<long long>(item) * kProbeItemTiles;
+        const long long t1 = t0 + kProbeItemTiles < ntiles ? t0 + kProbeItemTiles : ntiles;
+#pragma unroll 1
+        for (long long t = t0; t < t1; ++t) {
+          f4 v[U];
 #pragma unroll
-    for (int k = 0; k < U; ++k)
-      v[k] = (R > 0) ? (f4){0.f, 0.f, 0.f, 0.f} : (f4){1.f, 2.f, 3.f, static_cast<float>(t)};
-    if (R > 0) {
-      f4 tmp[R > 0 ? R : 1][U];
+          for (int k = 0; k < U; ++k)
+            v[k] = (R > 0) ? (f4){0.f, 0.f, 0.f, 0.f} : (f4){1.f, 2.f, 3.f, static_cast<float>(t)};
+          if (R > 0) {
+            f4 tmp[R > 0 ? R : 1][U];
 #pragma unroll
-      for (int r = 0; r < R; ++r)
+            for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int k = 0; k < U; ++k)
-          tmp[r][k] = load4_stream<true>(base + r * stride + t * tile + 4 * (k * kBlock + threadIdx.x), 4);
+              for (int k = 0; k < U; ++k)
+                tmp[r][k] = load4_stream<true>(base + r * stride + t * tile + 4 * (k * kBlock + threadIdx.x), 4);
 #pragma unroll
-      for (int r = 0; r < R; ++r)
+            for (int r = 0; r < R; ++r)
 #pragma unroll
-        for (int k = 0; k < U; ++k) v[k] += tmp[r][k];
-    }
-    if (W > 0) {
+              for (int k = 0; k < U; ++k) v[k] += tmp[r][k];
+          }
+          if (W > 0) {
 #pragma unroll
-      for (int w = 0; w < W; ++w)
+            for (int w = 0; w < W; ++w)
 #pragma unroll
-        for (int k = 0; k < U; ++k)
-          store4_stream<true>(base + (INPLACE ? w : R + w) * stride + t * tile + 4 * (k * kBlock + threadIdx.x),
-                              v[k] * static_cast<float>(w + 1), 4);
-    } else {
+              for (int k = 0; k < U; ++k)
+                store4_stream<true>(base + (INPLACE ? w : R + w) * stride + t * tile + 4 * (k * kBlock + threadIdx.x),
+                                    v[k] * static_cast<float>(w + 1), 4);
+          } else {
 #pragma unroll
-      for (int k = 0; k < U; ++k) acc += v[k];
-    }
-  }
+            for (int k = 0; k < U; ++k) acc += v[k];
+          }
+        }
+      },
+      [](int) {});
   if (W == 0 && acc.x + acc.y + acc.z + acc.w == 123.456f) sink[0] = acc.x;   // keeps the loads alive
 }
 

@@ -62,7 +62,7 @@ def load():
         "dppf_push_schedule": (f, [ctypes.c_int, f, i64, i64]),
         "dppf_util_copy": (ctypes.c_int, [vp, vp, i64, vp]),
         "dppf_util_stream_probe": (ctypes.c_int, [vp, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                                  ctypes.c_int, vp]),
+                                                  ctypes.c_int, ctypes.c_int, vp]),
         "dppf_plan_timing_enable": (ctypes.c_int, [vp, ctypes.c_int]),
         "dppf_plan_timing_read": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(f), ctypes.c_int]),
     }
@@ -275,10 +275,10 @@ def push_schedule(kind: str, push: float, t: int, t_total: int) -> float:
 
 
 def util_stream_probe(base, stride: int, n: int, reads: int, writes: int, inplace: bool, blocks_per_cu: int,
-                      stream=None) -> None:
+                      on_demand: bool = False, stream=None) -> None:
     """Launch the library's streaming probe (measurement aid, see include/dppf.h)."""
     _check(load().dppf_util_stream_probe(_dev(base), stride, n, reads, writes, 1 if inplace else 0, blocks_per_cu,
-                                         _stream(stream)), "dppf_util_stream_probe")
+                                         1 if on_demand else 0, _stream(stream)), "dppf_util_stream_probe")
 
 
 def layout_tiles(numel: Sequence[int]):

@@ -373,6 +373,65 @@ def test_round_captured_in_a_hip_graph_replays_like_eager_calls():
     plan_b.close()
 
 
+def test_on_demand_tail_is_reproducible_and_leaves_its_counter_clean():
+    # Lists with several tiles per block hand the tail of every read-write sweep out on demand
+    # (which block takes which tile then differs from run to run).  The results must not: the same
+    # bits every time, in eager calls and in replays of a captured graph whose kernels find the
+    # counter as the previous launch left it.
+    shapes = ((3_000_000,), (1_234_567,), (2_000_003,), (777,))
+    spec = W.small_spec(M=2, seed=91, shapes=shapes)
+    _, nfull, _ = dppf.layout_tiles(spec.numel)
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    assert nfull >= 4 * cus, "the list must be long enough for the on-demand part of the walk"
+    h = _hyper(spec)
+    inp = W.make_inputs(spec)
+    gk = inp.grads(0)
+    args = (h["lr"], h["mu"], h["wd"], h["pull"], h["push"])
+    ref_x, ref_v, ref_r, _, _ = O.dppf_round(np.stack(inp.x), np.stack(inp.v), np.stack(gk), *args)
+    plan = dppf.Plan(2, spec.numel)
+    outs = []
+    for _ in range(3):
+        x, v, g = _dev_rows(inp, inp.x), _dev_rows(inp, inp.v), _dev_rows(inp, gk)
+        r = torch.zeros(2, device="cuda")
+        plan.round(x, v, g, *args, r_out=r)
+        outs.append((download_rows(x), download_rows(v), r.cpu().numpy()))
+    assert_params_close(outs[0][0], ref_x, inp.offsets, 1, "x")
+    assert_rel(outs[0][2], ref_r, 1e-4, "r")
+    for o in outs[1:]:
+        assert all(np.array_equal(a, b) for a, b in zip(o, outs[0]))
+
+    # graph: a local step and a fused round (three kernels, so an odd number of launches per replay)
+    plan_b = dppf.Plan(2, spec.numel)
+    xa, va, ga = _dev_rows(inp, inp.x), _dev_rows(inp, inp.v), _dev_rows(inp, gk)
+    xb, vb, gb = _dev_rows(inp, inp.x), _dev_rows(inp, inp.v), _dev_rows(inp, gk)
+    ra, rb = torch.zeros(2, device="cuda"), torch.zeros(2, device="cuda")
+    ta = [dppf.PointerTable(t) for t in (xa, va, ga)]
+    tb = [dppf.PointerTable(t) for t in (xb, vb, gb)]
+
+    def both(p, t, r):
+        p.local_sgd_step(*t, h["lr"], h["mu"], h["wd"])
+        p.round(*t, *args, r_out=r)
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):                 # first call uploads the pointer tables
+        both(plan, ta, ra)
+    side.synchronize()
+    both(plan_b, tb, rb)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        both(plan, ta, ra)
+    for k in range(3):
+        graph.replay()
+        both(plan_b, tb, rb)
+        torch.cuda.synchronize()
+        assert np.array_equal(download_rows(xa), download_rows(xb)), f"replay {k}: x differs"
+        assert np.array_equal(download_rows(va), download_rows(vb)), f"replay {k}: v differs"
+        assert np.array_equal(ra.cpu().numpy(), rb.cpu().numpy()), f"replay {k}: r differs"
+    plan.close()
+    plan_b.close()
+
+
 @pytest.mark.parametrize("pull,push,wd", [(0.1, 0.5, 1e-3), (0.1, 0.75, 1e-3), (0.1, 1.0, 1e-4), (0.5, 5.0, 1e-4),
                                           (0.9, 9.0, 1e-4), (0.9, 90.0, 0.0), (1.0, 0.0, 1e-3), (0.05, 0.05, 0.0)])
 def test_fused_round_with_the_hyperparameters_the_paper_uses(pull, push, wd):
@@ -445,9 +504,17 @@ def test_measurement_utilities():
         buf[k * stride:k * stride + length] = float(k + 1)
     dppf.util_stream_probe(buf, stride, length, 4, 0, False, 1)   # read only: nothing changes
     assert torch.all(buf[4 * stride:] == 0)
-    assert lib.dppf_util_stream_probe(ctypes.c_void_p(buf.data_ptr()), stride, length, 3, 3, 0, 1, None) == -1
+    assert lib.dppf_util_stream_probe(ctypes.c_void_p(buf.data_ptr()), stride, length, 3, 3, 0, 1, 0, None) == -1
     dppf.util_stream_probe(buf, stride, length, 1, 1, False, 2)   # copy stream 0 -> stream 1
     assert torch.all(buf[stride:stride + length] == 1.0) and torch.all(buf[stride + length:2 * stride] == 0)
+    # the same with part of the work handed out on demand, on an array long enough for that
+    length = 16384 * 4096       # 1024 items of 16 tiles: four per block on 256 CUs
+    big = torch.zeros(3 * length, device="cuda")
+    big[:length] = torch.arange(length, device="cuda", dtype=torch.float32) % 1000.0
+    for _ in range(2):                                              # twice: the counter must come back clean
+        big[length:].zero_()
+        dppf.util_stream_probe(big, length, length, 1, 1, False, 1, on_demand=True)
+        assert torch.equal(big[length:2 * length], big[:length]) and torch.all(big[2 * length:] == 0)
 
 
 @pytest.mark.parametrize("M", [12, 17, 35])
