@@ -177,6 +177,90 @@ def test_fused_adamw_round(M):
     twin.close()
 
 
+LONG_SHAPES = ((2_500_000,), (1_234_567,), (1_000_003,), (777,))
+
+
+@pytest.mark.parametrize("M", [2, 17])
+def test_every_entry_point_on_a_list_with_an_on_demand_tail(M):
+    # With four or more tiles per thread block the read-write sweeps hand the tail of their tiles
+    # out on demand; every entry point must give the oracle's result through that path too
+    # (M = 17: the staged kernels for more workers than fit in registers).
+    spec = W.small_spec(M=M, seed=950 + M, shapes=LONG_SHAPES)
+    _, nfull, _ = dppf.layout_tiles(spec.numel)
+    assert nfull >= 4 * torch.cuda.get_device_properties(0).multi_processor_count
+    inp = W.make_inputs(spec)
+    gk = inp.grads(0)
+    x_host, v_host, g_host = np.stack(inp.x), np.stack(inp.v), np.stack(gk)
+    lr, mu, wd, pull, push = f32(0.1), f32(0.9), f32(1e-4), f32(0.3), f32(0.05)
+    plan = dppf.Plan(M, spec.numel)
+    r = torch.zeros(M, device="cuda")
+
+    # local step
+    x, v, g = _rows(inp, inp.x), _rows(inp, inp.v), _rows(inp, gk)
+    plan.local_sgd_step(x, v, g, lr, mu, wd)
+    ref_x1, ref_v1 = O.local_sgd_step(x_host, v_host, g_host, lr, mu, wd)
+    assert_params_close(download_rows(x), ref_x1, inp.offsets, 1, "local step x")
+    assert_params_close(download_rows(v), ref_v1, inp.offsets, 1, "local step v")
+
+    # round, then fused step + round
+    x = _rows(inp, inp.x)
+    plan.pull_push_round(x, pull, push, r_out=r)
+    ref_x, ref_r, ref_c, _ = O.pull_push_round(x_host, pull, push)
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+    assert_params_close(download_rows(x), ref_x, inp.offsets, 0, "round x", c=ref_c)
+    x, v = _rows(inp, inp.x), _rows(inp, inp.v)
+    plan.round(x, v, g, lr, mu, wd, pull, push, r_out=r)
+    ref_x, ref_v, ref_r, ref_c, _ = O.dppf_round(x_host, v_host, g_host, lr, mu, wd, pull, push)
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "fused r")
+    got = download_rows(x)
+    assert_params_close(got, ref_x, inp.offsets, 1, "fused round x", c=ref_c)
+    assert_params_close(download_rows(v), ref_v, inp.offsets, 1, "fused round v")
+    assert_update_close(got, ref_x, ref_x1, "fused round")
+
+    # exact two-term round
+    x = _rows(inp, inp.x)
+    plan.pull_push_round_exact(x, pull, f32(push * M), r_out=r)
+    ref_x, ref_r, _ = O.pull_push_round_exact(x_host, pull, f32(push * M))
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "exact r")
+    got = download_rows(x)
+    assert_params_close(got, ref_x, inp.offsets, 0, "exact round x")
+    assert_update_close(got, ref_x, x_host.astype(np.float64), "exact round")
+
+    # Alg. 1 literally, with a supplied consensus variable
+    rng = np.random.default_rng(3)
+    xc_host = (inp.x[0] + 2e-3 * rng.standard_normal(spec.d)).astype(np.float32)
+    xc = upload_tensors(xc_host, inp.offsets)
+    for push_from in ("average", "consensus"):
+        x = _rows(inp, inp.x)
+        plan.pull_then_push(x, xc, pull, push, push_from, r_post_out=r)
+        ref_x, ref_r = O.pull_then_push(x_host, xc_host, pull, push, push_from)
+        assert_rel(r.cpu().numpy(), ref_r, 1e-4, f"r_post ({push_from})")
+        got = download_rows(x)
+        assert_params_close(got, ref_x, inp.offsets, 0, f"pull_then_push x ({push_from})")
+        assert_update_close(got, ref_x, x_host.astype(np.float64), f"pull_then_push ({push_from})")
+
+    # AdamW step, then fused AdamW round
+    a_lr, b1, b2, eps, a_wd = f32(5e-4), f32(0.9), f32(0.999), f32(1e-8), f32(0.01)
+    x, m1, m2 = _rows(inp, inp.x), _rows(inp, inp.v), _rows(inp, inp.v)
+    plan.local_adamw_step(x, m1, m2, g, a_lr, b1, b2, eps, a_wd, 1)
+    zero = np.zeros_like(x_host, dtype=np.float64)
+    xo, ao, so = O.local_adamw_step(x_host.astype(np.float64), zero, zero, g_host, a_lr, b1, b2, eps, a_wd, 1)
+    assert_params_close(download_rows(x), xo, inp.offsets, 2, "adamw x")
+    assert_params_close(download_rows(m1), ao, inp.offsets, 2, "adamw m1")
+    assert_params_close(download_rows(m2), so, inp.offsets, 2, "adamw m2")
+    g2_host = np.stack(inp.grads(1))
+    g2 = _rows(inp, inp.grads(1))
+    plan.round_adamw(x, m1, m2, g2, a_lr, b1, b2, eps, a_wd, 2, f32(0.9), push, r_out=r)
+    x_pre, ao, so = O.local_adamw_step(xo, ao, so, g2_host, a_lr, b1, b2, eps, a_wd, 2)
+    ref_x, ref_r, ref_c, _ = O.pull_push_round(x_pre, f32(0.9), push)
+    assert_rel(r.cpu().numpy(), ref_r, 1e-4, "adamw round r")
+    got = download_rows(x)
+    assert_params_close(got, ref_x, inp.offsets, 4, "adamw round x", c=ref_c)
+    assert_params_close(download_rows(m2), so, inp.offsets, 4, "adamw round m2")
+    assert_update_close(got, ref_x, x_pre, "adamw round")
+    plan.close()
+
+
 def test_round_statistics_and_schedule():
     M = 5
     r_host = np.array([5.0, 5.0, 8.0, 0.0, 1.5], np.float32)
