@@ -223,7 +223,7 @@ int dppf_util_copy(float* dst, const float* src, int64_t n, void* stream);
  * starts at base + k*stride floats (base 16-byte aligned, stride >= n, multiple of 4).  Written
  * arrays are k = reads..reads+writes-1, or k = 0..writes-1 when inplace != 0 (the lane that read
  * an element overwrites it).  Only elements below the largest multiple of the probe's tile are
- * touched.  Supported (reads, writes): (1,0) (4,0) (12,0) (0,1) (0,4) (1,1) and, with or without
+ * touched.  Supported (reads, writes): (1,0) (4,0) (12,0) (0,1) (0,4) (1,1) (2,1) and, with or without
  * inplace, (4,4) (8,4) (12,4) (12,8), and in place only (16,8) (24,8); anything else returns
  * DPPF_EINVAL.  blocks_per_cu in 1..16.  on_demand = 0: the blocks split the work evenly;
  * on_demand != 0: they split the first half evenly and take the rest on demand, as the library's

@@ -13,7 +13,7 @@ import argparse
 import json
 import sys
 
-MIXES = [(1, 0, False), (4, 0, False), (12, 0, False), (0, 1, False), (0, 4, False), (1, 1, False),
+MIXES = [(1, 0, False), (4, 0, False), (12, 0, False), (0, 1, False), (0, 4, False), (1, 1, False), (2, 1, False),
          (4, 4, False), (4, 4, True), (8, 4, False), (8, 4, True), (12, 4, False), (12, 4, True),
          (12, 8, False), (12, 8, True), (16, 8, True), (24, 8, True)]
 

@@ -1051,6 +1051,7 @@ int dppf_util_stream_probe(float* base, int64_t stride, int64_t n, int reads, in
   DPPF_PROBE(0, 1, 4, false)
   DPPF_PROBE(0, 4, 4, false)
   DPPF_PROBE(1, 1, 4, false)
+  DPPF_PROBE(2, 1, 4, false)
   DPPF_PROBE(4, 4, 2, false)
   DPPF_PROBE(4, 4, 2, true)
   DPPF_PROBE(8, 4, 1, false)
