@@ -257,12 +257,13 @@ int keep_from_tile(const dppf_plan* p, int workers, KeepPolicy keep) {
   return tiles >= p->nfull ? 0 : p->nfull - static_cast<int>(tiles);
 }
 
-// 16-byte vectors a lane holds at once: M*U (plain), 2*M*U (update with the step), 3*M*U (fused).
-// Up to 8 workers the unroll keeps that at 16..24; 9..16 workers run without unrolling and still
-// fit the register file of a CU that holds one block (no spills).
+// U = 16-byte vectors of one worker that a lane handles per pass over a tile (a tile is four).  A
+// lane keeps M*U vectors of x; the fused sweeps add one worker's v and g (or AdamW's three) at a
+// time.  With one block per CU a lane may use the whole 512-entry register file; the values are
+// the fastest measured per range of M.
 constexpr int unroll_plain(int M) { return M <= 4 ? 4 : (M <= 8 ? 2 : 1); }
-constexpr int unroll_step_update(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }
-constexpr int unroll_fused(int M) { return M <= 2 ? 4 : (M <= 4 ? 2 : 1); }
+constexpr int unroll_step_update(int M) { return M <= 4 ? 4 : (M <= 8 ? 2 : 1); }
+constexpr int unroll_fused(int M) { return M <= 8 ? 4 : 2; }
 
 #define DPPF_SWITCH_M(m_value, ...)                                \
   switch (m_value) {                                               \
@@ -913,10 +914,10 @@ int dppf_round_adamw(dppf_plan* p, float* const* x, float* const* m1, float* con
   GridShape shape;
   if ((rc = timing_begin(p, DPPF_K_ADAMW_REDUCE, s))) return rc;
   DPPF_SWITCH_M(p->M, {
-    constexpr int kU = kM <= 2 ? 2 : 1;     // 4*M*U <= 32 vectors in flight
+    constexpr int kU = unroll_fused(kM);
     auto kern = k_adamw_reduce<kM, kU>;
     int gfull = 0;
-    if ((rc = grid_for(p, kern, 1, kBlocksPerCUHeavyMath, &gfull, &shape.grid))) return rc;
+    if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &shape.grid))) return rc;
     shape.walk = make_walk(p, gfull, 1, kOnDemandThird);
     hipLaunchKernelGGL(kern, dim3(shape.grid), dim3(kBlock), 0, s, p->tiles_dev, shape.walk, p->T,
                        (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), hp,
