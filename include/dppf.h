@@ -226,9 +226,10 @@ int dppf_util_copy(float* dst, const float* src, int64_t n, void* stream);
  * touched.  Supported (reads, writes): (1,0) (4,0) (12,0) (0,1) (0,4) (1,1) (2,1) and, with or without
  * inplace, (4,4) (8,4) (12,4) (12,8), and in place only (16,8) (24,8); anything else returns
  * DPPF_EINVAL.  blocks_per_cu in 1..16.  on_demand = 0: the blocks split the work evenly;
- * on_demand != 0: they split the first half evenly and take the rest on demand, as the library's
- * read-write sweeps do.  The probe keeps one counter per device: calls that could overlap on one
- * device (different streams) must not both use on_demand.
+ * on_demand != 0: they take work on demand the way the library's read-write sweeps do (the second
+ * half of it, or all of it when the launch moves more than about 2 GB).  The probe keeps one
+ * counter per device: calls that could overlap on one device (different streams) must not both
+ * use on_demand.
  * Timing is the caller's job (events around the call).  */
 int dppf_util_stream_probe(float* base, int64_t stride, int64_t n, int reads, int writes, int inplace,
                            int blocks_per_cu, int on_demand, void* stream);

@@ -204,31 +204,38 @@ int grid_for(dppf_plan* p, K kernel, int per_tile_items, int want_per_cu, int* g
 }
 
 // How much of a kernel's full-tile work is handed out on demand instead of being split evenly
-// (see walk_items).  Measured on the ViT-B-sized list: kernels that store nothing per item gain
-// most with half of the work on demand (sweep 2: -5 %); the fused reducing sweeps pay a block-wide
-// sum and a row of partial sums per on-demand tile and do best with a third (-2 %); the pure-read
-// reducing sweeps (a few microseconds per tile) lose more to that than they gain, so they keep the
-// even split.
-enum OnDemand { kOnDemandNone = 0, kOnDemandThird = 3, kOnDemandHalf = 2 };
-constexpr int kMinRoundsOnDemand = 4;   // fewer items per block than this: not worth a counter
+// (see walk_items).  Measured on the five lists:
+//  * with an even split the blocks of the slower dies finish last, and on the way there the
+//    blocks drift apart, so the part of the tile list (and of DRAM) the chip is working on at one
+//    moment widens; on demand the blocks stay on one compact window of consecutive tiles.
+//  * short launches lose a little per on-demand item (a barrier per item, per-tile partial sums
+//    in the reducing sweeps), long ones gain more than that from the compact window.
+// So: launches that move more than kAllOnDemandBytes hand out everything, shorter ones the second
+// half; the pure-read reducing sweeps (a few microseconds per tile, per-tile sums too dear) and
+// lists with fewer than kMinRoundsOnDemand items per block keep the even split.
+enum OnDemand { kEvenSplit, kOnDemand, kOnDemandReducing };
+constexpr int kMinRoundsOnDemand = 4;
+constexpr int kMinRoundsAllOnDemandReducing = 32;     // per-tile sums: only worth it on long lists
+constexpr double kAllOnDemandBytes = 2.2e9;           // about 0.4 ms of traffic
 
 // Items [0, returned value) of `count` are split evenly over `blocks` blocks, the rest handed out
-// on demand; returns count when nothing is.
-long long evenly_split_items(long long count, int blocks, OnDemand share) {
-  if (share == kOnDemandNone || blocks <= 0) return count;
+// on demand; returns count when nothing is.  bytes_per_item: what one item moves.
+long long evenly_split_items(long long count, int blocks, OnDemand policy, double bytes_per_item) {
+  if (policy == kEvenSplit || blocks <= 0) return count;
   const long long rounds = count / blocks;
   if (rounds < kMinRoundsOnDemand) return count;
-  const long long on_demand_rounds = (rounds + share - 1) / share;
-  return (rounds - on_demand_rounds) * blocks;
+  const bool all = static_cast<double>(count) * bytes_per_item >= kAllOnDemandBytes &&
+                   (policy != kOnDemandReducing || rounds >= kMinRoundsAllOnDemandReducing);
+  return all ? 0 : (rounds - (rounds + 1) / 2) * blocks;
 }
 
-Walk make_walk(const dppf_plan* p, int gfull, int per_tile_items, OnDemand share) {
+Walk make_walk(const dppf_plan* p, int gfull, int per_tile_items, OnDemand policy, double bytes_per_elem) {
   Walk w;
   w.nfull = p->nfull;
   w.ntiles = p->ntiles;
   w.gfull = gfull;
   const long long count = static_cast<long long>(p->nfull) * per_tile_items;
-  w.nstatic = static_cast<int>(evenly_split_items(count, gfull, share));
+  w.nstatic = static_cast<int>(evenly_split_items(count, gfull, policy, bytes_per_elem * kTileElems));
   w.sched = w.nstatic < count ? p->sched : nullptr;
   return w;
 }
@@ -308,7 +315,7 @@ int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const 
       int rc = grid_for(p, kern, 1, (SGD || XBAR == 1) ? kBlocksPerCUReadWrite : kBlocksPerCUReadOnly, &gfull,
                         &grid);
       if (rc) return rc;
-      walk = make_walk(p, gfull, 1, SGD ? kOnDemandThird : kOnDemandNone);
+      walk = make_walk(p, gfull, 1, SGD ? kOnDemandReducing : kEvenSplit, 16.0 * mg);
       if (shape) {
         shape->grid = grid;
         shape->walk = walk;
@@ -333,7 +340,7 @@ int launch_sweep2(dppf_plan* p, int mg, const void** xp, const void** vp, const 
     int grid = 0, gfull = 0;
     int rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid);
     if (rc) return rc;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandHalf), p->T, x, v, xb, lr,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemand, (STEP ? 12.0 : 8.0) * mg), p->T, x, v, xb, lr,
                        p->coef + m0, 1.0f / static_cast<float>(kM), p->partials, nparts, p->M, pull, push,
                        r_out, c_out);
   })
@@ -359,7 +366,7 @@ int launch_local_step(dppf_plan* p, const void** xp, const void** vp, const void
   if (rc) return rc;
   rc = timing_begin(p, DPPF_K_LOCAL_STEP, s);
   if (rc) return rc;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, p->M, kOnDemandHalf), p->M,
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, p->M, kOnDemand, 20.0), p->M,
                      p->T, (float* const*)(xp), (float* const*)(vp), (const float* const*)(gp), lr, mu, wd);
   HIP_TRY(hipGetLastError());
   return timing_end(p, s);
@@ -369,7 +376,7 @@ int launch_mean_any(dppf_plan* p, const void** xp, const void** xbarp, hipStream
   int grid = 0, gfull = 0;
   int rc = grid_for(p, k_mean_any, 1, kBlocksPerCUReadOnly, &gfull, &grid);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_mean_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandNone),
+  hipLaunchKernelGGL(k_mean_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kEvenSplit, 0.0),
                      p->M, p->T, (float* const*)(xp), (float* const*)(xbarp));
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
@@ -385,7 +392,7 @@ int launch_update_exact(dppf_plan* p, const void** xp, int nparts, float pull, f
     int grid = 0, gfull = 0;
     int rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid);
     if (rc) return rc;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandHalf), p->T, x,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemand, 8.0 * p->M), p->T, x,
                        p->partials, nparts, p->M, pull, push_r / mf, push_r / (mf * mf), r_out, c_out);
   })
   HIP_TRY(hipGetLastError());
@@ -408,7 +415,7 @@ int launch_seq(dppf_plan* p, int mg, int m0, const void** xp, const void** xcp, 
     if (WRITE) {
       auto kern = k_seq2<kM, kU, REF>;
       if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
-      hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandHalf), p->T, x,
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemand, 8.0 * mg + 4.0), p->T, x,
                          xc, rf, pull, keep, push, p->partials + m0, nparts, p->M,
                          r_post_out ? r_post_out + m0 : nullptr);
     } else {
@@ -416,7 +423,7 @@ int launch_seq(dppf_plan* p, int mg, int m0, const void** xp, const void** xcp, 
       if (shape->grid == 0) {     // later worker groups fill the same rows of the partial sums
         if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadOnly, &gfull, &grid))) return rc;
         shape->grid = grid;
-        shape->walk = make_walk(p, gfull, 1, kOnDemandNone);
+        shape->walk = make_walk(p, gfull, 1, kEvenSplit, 0.0);
       }
       hipLaunchKernelGGL(kern, dim3(shape->grid), dim3(kBlock), 0, s, p->tiles_dev, shape->walk, p->T, x, xc,
                          rf, pull, keep, p->partials + m0, p->M);
@@ -507,7 +514,7 @@ int launch_adamw_step(dppf_plan* p, const void** xd, const void** ad, const void
   int grid = 0, gfull = 0, rc;
   if ((rc = grid_for(p, kern, p->M, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
   if ((rc = timing_begin(p, DPPF_K_ADAMW_STEP, s))) return rc;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, p->M, kOnDemandHalf), p->M,
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, p->M, kOnDemand, 28.0), p->M,
                      p->T, (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), hp);
   HIP_TRY(hipGetLastError());
   return timing_end(p, s);
@@ -826,7 +833,7 @@ int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float 
     if ((rc = timing_begin(p, DPPF_K_UPDATE_EXACT, s))) return rc;
     int grid = 0, gfull = 0;
     if ((rc = grid_for(p, k_unit_sum_any, 1, kBlocksPerCUReadOnly, &gfull, &grid))) return rc;
-    hipLaunchKernelGGL(k_unit_sum_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandNone),
+    hipLaunchKernelGGL(k_unit_sum_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kEvenSplit, 0.0),
                        p->M, p->T, (float* const*)(xd), (const float* const*)(avg), p->coef, (float* const*)(usum));
     HIP_TRY(hipGetLastError());
     for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
@@ -836,7 +843,7 @@ int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float 
         constexpr int kU = unroll_plain(kM) > 2 ? 2 : unroll_plain(kM);
         auto kern = k_update_exact_given<kM, kU>;
         if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemandHalf), p->T, xg,
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemand, 8.0 * mg + 8.0), p->T, xg,
                            (const float* const*)(avg), (const float* const*)(usum), p->coef + m0, push_r / (mf * mf));
       })
       HIP_TRY(hipGetLastError());
@@ -918,7 +925,7 @@ int dppf_round_adamw(dppf_plan* p, float* const* x, float* const* m1, float* con
     auto kern = k_adamw_reduce<kM, kU>;
     int gfull = 0;
     if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &shape.grid))) return rc;
-    shape.walk = make_walk(p, gfull, 1, kOnDemandThird);
+    shape.walk = make_walk(p, gfull, 1, kOnDemandReducing, 28.0 * p->M);
     hipLaunchKernelGGL(kern, dim3(shape.grid), dim3(kBlock), 0, s, p->tiles_dev, shape.walk, p->T,
                        (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), hp,
                        p->partials, p->M);
@@ -1039,7 +1046,8 @@ int dppf_util_stream_probe(float* base, int64_t stride, int64_t n, int reads, in
     walk_.nfull = walk_.ntiles = static_cast<int>(items_);                                       \
     walk_.gfull = static_cast<int>(grid.x);                                                      \
     walk_.nstatic = static_cast<int>(                                                            \
-        evenly_split_items(items_, walk_.gfull, on_demand ? kOnDemandHalf : kOnDemandNone));     \
+        evenly_split_items(items_, walk_.gfull, on_demand ? kOnDemand : kEvenSplit,              \
+                           4.0 * kProbeItemTiles * kBlock * U_ * 4 * (R_ + W_)));                \
     walk_.sched = walk_.nstatic < items_ ? sched : nullptr;                                      \
     hipLaunchKernelGGL((k_probe<R_, W_, U_, IP_>), grid, block, 0, s, base, static_cast<long long>(stride), \
                        static_cast<long long>(n), sink, walk_);                                  \

@@ -187,7 +187,7 @@ using PartialTile = std::integral_constant<bool, false>;
 // holds never depend on which block took which item -- results stay bit-reproducible.
 template <bool REVERSE, typename Body, typename Flush>
 __device__ __forceinline__ void walk_items(const Walk& w, int per_tile, Body&& body, Flush&& flush) {
-  __shared__ int s_next;
+  __shared__ int s_next[2];
   const bool full = static_cast<int>(blockIdx.x) < w.gfull;
   const int me = full ? static_cast<int>(blockIdx.x) : static_cast<int>(blockIdx.x) - w.gfull;
   const int lanes = full ? w.gfull : static_cast<int>(gridDim.x) - w.gfull;
@@ -210,6 +210,8 @@ __device__ __forceinline__ void walk_items(const Walk& w, int per_tile, Body&& b
   if (ndyn > 0 && threadIdx.x == 0) fetched = atomicAdd(&w.sched->next, 1u);
   int j = REVERSE ? last_owned : me;
   bool on_demand = false;
+  int slot = 0;   // the item number travels from thread 0 to the block through two alternating words:
+                  // one barrier per item is enough, the next write goes to the other word
   for (;;) {
     if (!on_demand && (REVERSE ? j < lo : j >= lo + w.nstatic)) {
       flush(static_cast<int>(blockIdx.x));
@@ -218,10 +220,10 @@ __device__ __forceinline__ void walk_items(const Walk& w, int per_tile, Body&& b
     }
     int k = 0;
     if (on_demand) {
-      if (threadIdx.x == 0) s_next = static_cast<int>(fetched);
+      if (threadIdx.x == 0) s_next[slot] = static_cast<int>(fetched);
       __syncthreads();
-      k = s_next;
-      __syncthreads();
+      k = s_next[slot];
+      slot ^= 1;
       if (k >= ndyn) break;            // every block gets here: the counter only grows
       if (threadIdx.x == 0) fetched = atomicAdd(&w.sched->next, 1u);   // the one after, while this one runs
       j = REVERSE ? ndyn - 1 - k : w.nstatic + k;
