@@ -250,14 +250,12 @@ struct GridShape {
 
 // Which of sweep 1's x loads go through the caches (see k_sweep1).
 enum KeepPolicy {
-  kKeepAll,      // every tile: sweep 2 follows and the loads are not the bottleneck (fused sweep 1)
   kKeepTail,     // only the tiles touched last, as many as fit the last-level cache budget
   kKeepNone      // nothing reads x again soon
 };
 constexpr long long kLastLevelCacheBudget = 256ll << 20;   // bytes of x worth keeping (the cache is 256 MB)
 
 int keep_from_tile(const dppf_plan* p, int workers, KeepPolicy keep) {
-  if (keep == kKeepAll) return 0;
   if (keep == kKeepNone) return p->nfull;
   const long long per_tile = static_cast<long long>(workers) * kTileElems * sizeof(float);
   const long long tiles = kLastLevelCacheBudget / per_tile;
@@ -546,8 +544,8 @@ int round_impl(dppf_plan* p, bool with_step, float* const* x, float* const* v, c
   if (p->M <= kMaxTemplM) {
     if ((rc = timing_begin(p, with_step ? DPPF_K_STEP_REDUCE : DPPF_K_REDUCE, s))) return rc;
     if (with_step) {
-      rc = xbar_out ? launch_sweep1<true, 1, true>(p, p->M, xd, vd, gd, xbd, lr, mu, wd, 0, kKeepAll, &shape, s)
-                    : launch_sweep1<true, 0, true>(p, p->M, xd, vd, gd, nullptr, lr, mu, wd, 0, kKeepAll, &shape, s);
+      rc = xbar_out ? launch_sweep1<true, 1, true>(p, p->M, xd, vd, gd, xbd, lr, mu, wd, 0, kKeepTail, &shape, s)
+                    : launch_sweep1<true, 0, true>(p, p->M, xd, vd, gd, nullptr, lr, mu, wd, 0, kKeepTail, &shape, s);
     } else {
       rc = xbar_out ? launch_sweep1<false, 1, true>(p, p->M, xd, nullptr, nullptr, xbd, 0, 0, 0, 0, kKeepTail, &shape, s)
                     : launch_sweep1<false, 0, true>(p, p->M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, kKeepTail, &shape, s);
