@@ -209,13 +209,24 @@ def test_every_entry_point_on_a_list_with_an_on_demand_tail(M):
     assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
     assert_params_close(download_rows(x), ref_x, inp.offsets, 0, "round x", c=ref_c)
     x, v = _rows(inp, inp.x), _rows(inp, inp.v)
-    plan.round(x, v, g, lr, mu, wd, pull, push, r_out=r)
-    ref_x, ref_v, ref_r, ref_c, _ = O.dppf_round(x_host, v_host, g_host, lr, mu, wd, pull, push)
+    xbar = upload_tensors(np.zeros(spec.d, np.float32), inp.offsets)
+    plan.round(x, v, g, lr, mu, wd, pull, push, r_out=r, xbar_out=xbar)
+    ref_x, ref_v, ref_r, ref_c, ref_avg = O.dppf_round(x_host, v_host, g_host, lr, mu, wd, pull, push)
     assert_rel(r.cpu().numpy(), ref_r, 1e-4, "fused r")
+    assert_params_close(download(xbar)[None, :], ref_avg[None, :], inp.offsets, 1, "fused round average")
     got = download_rows(x)
     assert_params_close(got, ref_x, inp.offsets, 1, "fused round x", c=ref_c)
     assert_params_close(download_rows(v), ref_v, inp.offsets, 1, "fused round v")
     assert_update_close(got, ref_x, ref_x1, "fused round")
+
+    # the stand-alone average and distances
+    x = _rows(inp, inp.x)
+    plan.replica_mean(x, xbar)
+    assert_params_close(download(xbar)[None, :], O.replica_mean(x_host)[None, :], inp.offsets, 0, "average")
+    for given in (None, xbar):
+        r.zero_()
+        plan.dist_norms(x, r, xbar=given)
+        assert_rel(r.cpu().numpy(), O.dist_norms(x_host, O.replica_mean(x_host)), 1e-4, "distances")
 
     # exact two-term round
     x = _rows(inp, inp.x)
