@@ -24,7 +24,9 @@
  *    PLACE.  The library never allocates, frees or resizes caller memory.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *    ENQUEUE work on it and return without waiting for the GPU.  A plan must not be used
- *    from two streams or two host threads at the same time (it owns scratch buffers).
+ *    from two streams or two host threads at the same time (it owns scratch buffers and the
+ *    counter its kernels take their work from); neither may a captured graph that uses a plan
+ *    run at the same time as other work on that plan.
  *  - Calls may be captured into a HIP graph, provided one eager call with the same pointer
  *    tables was made before (a new table is uploaded with an event wait that capture forbids).
  *  - Small outputs r_out / c_out are DEVICE arrays of M floats, written by the enqueued work.
