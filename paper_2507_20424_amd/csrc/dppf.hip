@@ -229,13 +229,21 @@ long long evenly_split_items(long long count, int blocks, OnDemand policy, doubl
   return all ? 0 : (rounds - (rounds + 1) / 2) * blocks;
 }
 
-Walk make_walk(const dppf_plan* p, int gfull, int per_tile_items, OnDemand policy, double bytes_per_elem) {
+// Kernels that take all workers of a tile together: one item per full tile (workers_per_tile = 1,
+// tiles_per_item = 1).  Kernels that take one worker at a time: one item per worker and
+// kTilesPerWorkerItem full tiles (workers_per_tile = M) -- the kernel's own arithmetic on item
+// numbers assumes exactly that, whatever M is.  bytes_per_elem: what a kernel moves per tile element.
+Walk make_walk(const dppf_plan* p, int gfull, int workers_per_tile, int tiles_per_item, OnDemand policy,
+               double bytes_per_elem) {
   Walk w;
   w.nfull = p->nfull;
   w.ntiles = p->ntiles;
   w.gfull = gfull;
-  const long long count = static_cast<long long>(p->nfull) * per_tile_items;
-  w.nstatic = static_cast<int>(evenly_split_items(count, gfull, policy, bytes_per_elem * kTileElems));
+  const long long count =
+      static_cast<long long>((p->nfull + tiles_per_item - 1) / tiles_per_item) * workers_per_tile;
+  w.nitems = static_cast<int>(count);
+  w.nstatic = static_cast<int>(
+      evenly_split_items(count, gfull, policy, bytes_per_elem * kTileElems * tiles_per_item));
   w.sched = w.nstatic < count ? p->sched : nullptr;
   return w;
 }
@@ -245,7 +253,7 @@ Walk make_walk(const dppf_plan* p, int gfull, int per_tile_items, OnDemand polic
 struct GridShape {
   int grid = 0;
   Walk walk{};
-  int nparts() const { return grid + (walk.nfull - walk.nstatic); }   // reducing sweeps have one item per tile
+  int nparts() const { return grid + (walk.nitems - walk.nstatic); }
 };
 
 // Which of sweep 1's x loads go through the caches (see k_sweep1).
@@ -313,7 +321,7 @@ int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const 
       int rc = grid_for(p, kern, 1, (SGD || XBAR == 1) ? kBlocksPerCUReadWrite : kBlocksPerCUReadOnly, &gfull,
                         &grid);
       if (rc) return rc;
-      walk = make_walk(p, gfull, 1, SGD ? kOnDemandReducing : kEvenSplit, 16.0 * mg);
+      walk = make_walk(p, gfull, 1, 1, SGD ? kOnDemandReducing : kEvenSplit, 16.0 * mg);
       if (shape) {
         shape->grid = grid;
         shape->walk = walk;
@@ -338,7 +346,7 @@ int launch_sweep2(dppf_plan* p, int mg, const void** xp, const void** vp, const 
     int grid = 0, gfull = 0;
     int rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid);
     if (rc) return rc;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemand, (STEP ? 12.0 : 8.0) * mg), p->T, x, v, xb, lr,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, 1, kOnDemand, (STEP ? 12.0 : 8.0) * mg), p->T, x, v, xb, lr,
                        p->coef + m0, 1.0f / static_cast<float>(kM), p->partials, nparts, p->M, pull, push,
                        r_out, c_out);
   })
@@ -364,7 +372,7 @@ int launch_local_step(dppf_plan* p, const void** xp, const void** vp, const void
   if (rc) return rc;
   rc = timing_begin(p, DPPF_K_LOCAL_STEP, s);
   if (rc) return rc;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, p->M, kOnDemand, 20.0), p->M,
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, p->M, kTilesPerWorkerItem, kOnDemand, 20.0), p->M,
                      p->T, (float* const*)(xp), (float* const*)(vp), (const float* const*)(gp), lr, mu, wd);
   HIP_TRY(hipGetLastError());
   return timing_end(p, s);
@@ -374,7 +382,7 @@ int launch_mean_any(dppf_plan* p, const void** xp, const void** xbarp, hipStream
   int grid = 0, gfull = 0;
   int rc = grid_for(p, k_mean_any, 1, kBlocksPerCUReadOnly, &gfull, &grid);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_mean_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kEvenSplit, 0.0),
+  hipLaunchKernelGGL(k_mean_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, 1, kEvenSplit, 0.0),
                      p->M, p->T, (float* const*)(xp), (float* const*)(xbarp));
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
@@ -390,7 +398,7 @@ int launch_update_exact(dppf_plan* p, const void** xp, int nparts, float pull, f
     int grid = 0, gfull = 0;
     int rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid);
     if (rc) return rc;
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemand, 8.0 * p->M), p->T, x,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, 1, kOnDemand, 8.0 * p->M), p->T, x,
                        p->partials, nparts, p->M, pull, push_r / mf, push_r / (mf * mf), r_out, c_out);
   })
   HIP_TRY(hipGetLastError());
@@ -413,7 +421,7 @@ int launch_seq(dppf_plan* p, int mg, int m0, const void** xp, const void** xcp, 
     if (WRITE) {
       auto kern = k_seq2<kM, kU, REF>;
       if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
-      hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemand, 8.0 * mg + 4.0), p->T, x,
+      hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, 1, kOnDemand, 8.0 * mg + 4.0), p->T, x,
                          xc, rf, pull, keep, push, p->partials + m0, nparts, p->M,
                          r_post_out ? r_post_out + m0 : nullptr);
     } else {
@@ -421,7 +429,7 @@ int launch_seq(dppf_plan* p, int mg, int m0, const void** xp, const void** xcp, 
       if (shape->grid == 0) {     // later worker groups fill the same rows of the partial sums
         if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadOnly, &gfull, &grid))) return rc;
         shape->grid = grid;
-        shape->walk = make_walk(p, gfull, 1, kEvenSplit, 0.0);
+        shape->walk = make_walk(p, gfull, 1, 1, kEvenSplit, 0.0);
       }
       hipLaunchKernelGGL(kern, dim3(shape->grid), dim3(kBlock), 0, s, p->tiles_dev, shape->walk, p->T, x, xc,
                          rf, pull, keep, p->partials + m0, p->M);
@@ -512,7 +520,7 @@ int launch_adamw_step(dppf_plan* p, const void** xd, const void** ad, const void
   int grid = 0, gfull = 0, rc;
   if ((rc = grid_for(p, kern, p->M, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
   if ((rc = timing_begin(p, DPPF_K_ADAMW_STEP, s))) return rc;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, p->M, kOnDemand, 28.0), p->M,
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, p->M, kTilesPerWorkerItem, kOnDemand, 28.0), p->M,
                      p->T, (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), hp);
   HIP_TRY(hipGetLastError());
   return timing_end(p, s);
@@ -831,7 +839,7 @@ int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float 
     if ((rc = timing_begin(p, DPPF_K_UPDATE_EXACT, s))) return rc;
     int grid = 0, gfull = 0;
     if ((rc = grid_for(p, k_unit_sum_any, 1, kBlocksPerCUReadOnly, &gfull, &grid))) return rc;
-    hipLaunchKernelGGL(k_unit_sum_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kEvenSplit, 0.0),
+    hipLaunchKernelGGL(k_unit_sum_any, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, 1, kEvenSplit, 0.0),
                        p->M, p->T, (float* const*)(xd), (const float* const*)(avg), p->coef, (float* const*)(usum));
     HIP_TRY(hipGetLastError());
     for (int m0 = 0; m0 < p->M; m0 += kMaxTemplM) {
@@ -841,7 +849,7 @@ int dppf_pull_push_round_exact(dppf_plan* p, float* const* x, float pull, float 
         constexpr int kU = unroll_plain(kM) > 2 ? 2 : unroll_plain(kM);
         auto kern = k_update_exact_given<kM, kU>;
         if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &grid))) return rc;
-        hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, kOnDemand, 8.0 * mg + 8.0), p->T, xg,
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, make_walk(p, gfull, 1, 1, kOnDemand, 8.0 * mg + 8.0), p->T, xg,
                            (const float* const*)(avg), (const float* const*)(usum), p->coef + m0, push_r / (mf * mf));
       })
       HIP_TRY(hipGetLastError());
@@ -923,7 +931,7 @@ int dppf_round_adamw(dppf_plan* p, float* const* x, float* const* m1, float* con
     auto kern = k_adamw_reduce<kM, kU>;
     int gfull = 0;
     if ((rc = grid_for(p, kern, 1, kBlocksPerCUReadWrite, &gfull, &shape.grid))) return rc;
-    shape.walk = make_walk(p, gfull, 1, kOnDemandReducing, 28.0 * p->M);
+    shape.walk = make_walk(p, gfull, 1, 1, kOnDemandReducing, 28.0 * p->M);
     hipLaunchKernelGGL(kern, dim3(shape.grid), dim3(kBlock), 0, s, p->tiles_dev, shape.walk, p->T,
                        (float* const*)(xd), (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), hp,
                        p->partials, p->M);
@@ -1041,7 +1049,7 @@ int dppf_util_stream_probe(float* base, int64_t stride, int64_t n, int reads, in
     const long long tiles_ = n / (static_cast<long long>(kBlock) * U_ * 4);                      \
     const long long items_ = (tiles_ + kProbeItemTiles - 1) / kProbeItemTiles;                   \
     Walk walk_;                                                                                  \
-    walk_.nfull = walk_.ntiles = static_cast<int>(items_);                                       \
+    walk_.nfull = walk_.ntiles = walk_.nitems = static_cast<int>(items_);                        \
     walk_.gfull = static_cast<int>(grid.x);                                                      \
     walk_.nstatic = static_cast<int>(                                                            \
         evenly_split_items(items_, walk_.gfull, on_demand ? kOnDemand : kEvenSplit,              \

@@ -177,6 +177,32 @@ def test_fused_adamw_round(M):
     twin.close()
 
 
+@pytest.mark.parametrize("M", [1, 3])
+@pytest.mark.parametrize("shapes", [((4096,),), ((3 * 4096 + 5,), (17,)), ((4096,), (2 * 4096,), (100,), (2 * 4096 + 1,))])
+def test_local_steps_take_full_tiles_in_pairs(M, shapes):
+    # the local-step kernels handle one worker at a time, two full tiles per work item: lists with
+    # one, three and five full tiles leave a single tile over, for one worker as for several
+    spec = W.small_spec(M=M, seed=640 + M + len(shapes), shapes=shapes)
+    inp = W.make_inputs(spec)
+    gk = inp.grads(0)
+    x_host, v_host, g_host = np.stack(inp.x), np.stack(inp.v), np.stack(gk)
+    plan = dppf.Plan(M, spec.numel)
+    x, v, g = _rows(inp, inp.x), _rows(inp, inp.v), _rows(inp, gk)
+    plan.local_sgd_step(x, v, g, f32(0.1), f32(0.9), f32(1e-3))
+    ref_x, ref_v = O.local_sgd_step(x_host, v_host, g_host, f32(0.1), f32(0.9), f32(1e-3))
+    assert_params_close(download_rows(x), ref_x, inp.offsets, 1, "x")
+    assert_params_close(download_rows(v), ref_v, inp.offsets, 1, "v")
+    lr, b1, b2, eps, wd = f32(5e-4), f32(0.9), f32(0.999), f32(1e-8), f32(0.01)
+    x, m1, m2 = _rows(inp, inp.x), _rows(inp, inp.v), _rows(inp, inp.v)
+    plan.local_adamw_step(x, m1, m2, g, lr, b1, b2, eps, wd, 1)
+    zero = np.zeros_like(x_host, dtype=np.float64)
+    xo, ao, so = O.local_adamw_step(x_host.astype(np.float64), zero, zero, g_host, lr, b1, b2, eps, wd, 1)
+    assert_params_close(download_rows(x), xo, inp.offsets, 2, "adamw x")
+    assert_params_close(download_rows(m1), ao, inp.offsets, 2, "adamw m1")
+    assert_params_close(download_rows(m2), so, inp.offsets, 2, "adamw m2")
+    plan.close()
+
+
 LONG_SHAPES = ((2_500_000,), (1_234_567,), (1_000_003,), (777,))
 
 
