@@ -55,7 +55,7 @@ def main() -> int:
                      "GBps_on_demand": round(best[True][0], 1), "blocks_per_cu_on_demand": best[True][1],
                      "footprint_GB": round(4.0 * n * streams / 1e9, 2)})
         print(f"R={reads:2d} W={writes:2d} {'in place' if inplace else '        '}  even split {best[False][0]:7.0f} GB/s "
-              f"({100 * best[False][0] / 8000:.1f} %) at {best[False][1]} block(s)/CU;  tail on demand "
+              f"({100 * best[False][0] / 8000:.1f} %) at {best[False][1]} block(s)/CU;  on demand "
               f"{best[True][0]:7.0f} GB/s ({100 * best[True][0] / 8000:.1f} %) at {best[True][1]} block(s)/CU;  "
               f"footprint {4.0 * n * streams / 1e9:.2f} GB", flush=True)
     print(json.dumps({"probe": rows}))
