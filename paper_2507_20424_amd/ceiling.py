@@ -4,8 +4,8 @@
 
 Runs the library's streaming probe (``dppf_util_stream_probe``) over a footprint far larger than
 the last-level cache and prints, per mix, the best rate over 1, 2 and 8 resident blocks per CU,
-once with the work split evenly over the blocks and once with the work handed out on demand.  These are the ceilings the DPPF kernels are compared with next to the 8 TB/s datasheet
-peak."""
+once with the work split evenly over the blocks and once with the work handed out on demand.
+These are the ceilings the DPPF kernels are compared with next to the 8 TB/s datasheet peak."""
 from __future__ import annotations
 
 import argparse
