@@ -170,15 +170,22 @@ def pull_push_round_exact(x, pull, push_r):
 # Round by-products the paper logs (appendix "Pull-Push Mechanism") and the push-strength
 # schedules (appendix "How to Schedule The Pushing Force?").
 # --------------------------------------------------------------------------------------
-def round_statistics(r, pull, push):
+def round_statistics(r, pull, push, x_avg=None):
     """Relaxed MV (mean distance to the average), per-worker pull strength alpha*r_m and
-    push strength lambda."""
+    push strength lambda.  With the average x_A given, also its Euclidean norm ||x_A||_2 and
+    the ratio of the valley width (the relaxed MV) to that norm, the two quantities the
+    appendix section on hyper-parameter sensitivity tracks."""
     r = _as_f64(r)
-    return {
+    out = {
         "relaxed_mv": float(np.sum(r) / r.shape[0]),
         "pull_strength": pull * r,
         "push_strength": np.full(r.shape, float(push)),
     }
+    if x_avg is not None:
+        x_avg = _as_f64(x_avg)
+        out["average_norm"] = float(np.sqrt(np.sum(x_avg * x_avg)))
+        out["width_over_norm"] = out["relaxed_mv"] / out["average_norm"]
+    return out
 
 
 def push_schedule(kind, push, t, t_total):
