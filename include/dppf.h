@@ -189,6 +189,27 @@ int dppf_round_flat(dppf_plan* plan, float* x, float* v, const float* g, int64_t
                     float* r_out, float* c_out, float* xbar_out, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * For callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc: dppf_pull_push_round_flat without a plan.
+ * Same arithmetic and same kernels as dppf_pull_push_round_flat (x: DEVICE, worker m's vector
+ * of d floats starts at x + m*ld, ld >= d, updated in place; r_out, c_out: DEVICE, M floats,
+ * optional), but every buffer a plan would own -- tile list, pointer table, partial sums,
+ * work counter -- lives in a device array of DPPF_STATIC_SCRATCH_BYTES bytes that is part of
+ * the library image (each GPU the library is used on holds its own copy until the process
+ * ends).  The call allocates nothing on the device and nothing on the host, copies nothing
+ * from host memory and issues no memset: it enqueues kernels only.
+ * Limits: M <= DPPF_STATIC_MAX_WORKERS and d <= DPPF_STATIC_MAX_DIM, else DPPF_ELIMIT and
+ * nothing is enqueued.  All calls on one GPU share that GPU's array, which keeps the last
+ * call's contents (each call rewrites what it reads): two such calls that could overlap on one
+ * GPU (different streams, or two threads) race and must be serialised by the caller.
+ * ------------------------------------------------------------------------------------- */
+#define DPPF_STATIC_MAX_WORKERS 16
+#define DPPF_STATIC_MAX_DIM 134217728            /* 2^27 elements per worker */
+#define DPPF_STATIC_SCRATCH_BYTES 787456
+int dppf_pull_push_round_flat_static(float* x, int M, int64_t d, int64_t ld, float pull, float push,
+                                     float* r_out, float* c_out, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Per-kernel timing with HIP events on the caller's stream (for benchmarks).  While
  * enabled, every kernel the plan launches is bracketed by two events.  dppf_plan_timing_read
  * waits for the recorded work, then returns up to `cap` records of the launches made since

@@ -35,6 +35,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <utility>
 #include <vector>
@@ -73,6 +74,40 @@ struct TimingRec {
   hipEvent_t start, stop;
 };
 
+// What the library remembers per device for the life of the process, in fixed-size storage (the
+// entry point that must not allocate uses it too): resident blocks per CU of every kernel that has
+// been launched there, and the address of that device's copy of the static scratch array.
+constexpr int kMaxDevices = 64;
+constexpr int kOccupancySlots = 1024;
+struct DeviceState {
+  int num_cu = 0;
+  int nocc = 0;
+  const void* occ_kernel[kOccupancySlots];
+  int occ_per_cu[kOccupancySlots];
+  unsigned char* static_scratch = nullptr;
+};
+DeviceState g_device[kMaxDevices];
+std::mutex g_device_mutex;
+
+// Scratch memory of dppf_pull_push_round_flat_static, the entry point for callers that may not
+// allocate: a file-scope device array (every GPU the library runs on holds its own copy until the
+// process ends).  Host code never uses the array's name as an address; it asks the runtime for
+// this device's copy once (static_scratch_base) and passes that pointer to the kernels.
+constexpr long long kStaticMaxDim = 1ll << 27;              // elements per worker
+constexpr int kStaticMaxWorkers = kMaxTemplM;
+constexpr int kStaticMaxTiles = static_cast<int>(kStaticMaxDim / kTileElems) + 1;
+constexpr int kStaticMaxRows = 2048;                        // rows of partial sums (one per block)
+constexpr size_t round_up_256(size_t n) { return (n + 255) / 256 * 256; }
+constexpr size_t kStaticOffSched = 0;
+constexpr size_t kStaticOffCoef = kStaticOffSched + round_up_256(sizeof(Sched));
+constexpr size_t kStaticOffPtrs = kStaticOffCoef + round_up_256(sizeof(Coef) * kStaticMaxWorkers);
+constexpr size_t kStaticOffTiles = kStaticOffPtrs + round_up_256(sizeof(float*) * kStaticMaxWorkers);
+constexpr size_t kStaticOffPartials = kStaticOffTiles + round_up_256(sizeof(Tile) * (kStaticMaxTiles + 1));
+constexpr size_t kStaticBytes =
+    kStaticOffPartials + round_up_256(sizeof(double) * kStaticMaxRows * kStaticMaxWorkers);
+static_assert(kStaticBytes == DPPF_STATIC_SCRATCH_BYTES, "the header documents the size of the static scratch");
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticBytes];
+
 }  // namespace
 
 struct dppf_plan {
@@ -93,8 +128,6 @@ struct dppf_plan {
   std::vector<long long> tensor_offset;     // start of tensor t inside xbar_scratch
   enum Role { RX = 0, RV, RG, RM1, RM2, RXBAR, RXBAR_SCRATCH, RUSUM_SCRATCH, RXC, NROLES };
   PtrTable tab[NROLES];
-  // resident blocks per CU of each kernel that has been launched (queried once)
-  std::vector<std::pair<const void*, int>> occupancy;
   // timing
   bool timing = false;
   std::vector<TimingRec> recs;
@@ -180,12 +213,21 @@ template <typename K>
 int grid_for(dppf_plan* p, K kernel, int per_tile_items, int want_per_cu, int* gfull_out, int* grid_out) {
   int per_cu = 0;
   const void* key = reinterpret_cast<const void*>(kernel);
-  for (const auto& kv : p->occupancy)
-    if (kv.first == key) per_cu = kv.second;
-  if (per_cu == 0) {
-    HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBlock, 0));
-    if (per_cu < 1) per_cu = 1;
-    p->occupancy.emplace_back(key, per_cu);
+  if (p->device < 0 || p->device >= kMaxDevices) return DPPF_ELIMIT;
+  {
+    std::lock_guard<std::mutex> lock(g_device_mutex);
+    DeviceState& dev = g_device[p->device];
+    for (int i = 0; i < dev.nocc; ++i)
+      if (dev.occ_kernel[i] == key) per_cu = dev.occ_per_cu[i];
+    if (per_cu == 0) {
+      HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBlock, 0));
+      if (per_cu < 1) per_cu = 1;
+      if (dev.nocc < kOccupancySlots) {      // a full table only means the query is repeated
+        dev.occ_kernel[dev.nocc] = key;
+        dev.occ_per_cu[dev.nocc] = per_cu;
+        ++dev.nocc;
+      }
+    }
   }
   if (per_cu < 1) per_cu = 1;
   if (per_cu > want_per_cu) per_cu = want_per_cu;
@@ -327,6 +369,7 @@ int launch_sweep1(dppf_plan* p, int mg, const void** xp, const void** vp, const 
         shape->walk = walk;
       }
     }
+    if (grid + (walk.nitems - walk.nstatic) > p->partials_rows) return DPPF_ELIMIT;   // rows of partial sums
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->tiles_dev, walk, p->T, x, v, g, xb,
                        lr, mu, wd, p->partials + m0, p->M, keep_from_tile(p, mg, keep));
   })
@@ -1009,6 +1052,67 @@ int dppf_round_flat(dppf_plan* p, float* x, float* v, const float* g, int64_t ld
   float* xb[1] = {xbar_out};
   return dppf_round(p, xt.data(), vt.data(), gt.data(), lr, momentum, weight_decay, pull, push, r_out,
                     c_out, xbar_out ? xb : nullptr, stream);
+} DPPF_CATCH
+
+// ---- the plain round on one flat buffer, for callers that may not allocate
+// This device's copy of the static scratch array and its CU count, looked up once per device.
+static int static_scratch_base(int device, unsigned char** base, int* num_cu) {
+  if (device < 0 || device >= kMaxDevices) return DPPF_ELIMIT;
+  std::lock_guard<std::mutex> lock(g_device_mutex);
+  DeviceState& dev = g_device[device];
+  if (!dev.static_scratch) {
+    void* ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch)));   // of the CURRENT device
+    if (!ptr) return DPPF_EHIP;
+    dev.static_scratch = static_cast<unsigned char*>(ptr);
+  }
+  if (dev.num_cu == 0)
+    HIP_TRY(hipDeviceGetAttribute(&dev.num_cu, hipDeviceAttributeMultiprocessorCount, device));
+  *base = dev.static_scratch;
+  *num_cu = dev.num_cu;
+  return DPPF_OK;
+}
+
+int dppf_pull_push_round_flat_static(float* x, int M, int64_t d, int64_t ld, float pull, float push,
+                                     float* r_out, float* c_out, void* stream) try {
+  if (M < 1 || d < 0 || ld < d || (d > 0 && !x)) return DPPF_EINVAL;
+  if (reinterpret_cast<uintptr_t>(x) & 3u) return DPPF_EINVAL;
+  if (M > kStaticMaxWorkers || d > kStaticMaxDim) return DPPF_ELIMIT;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int device = -1, num_cu = 0, rc;
+  HIP_TRY(hipGetDevice(&device));
+  unsigned char* base = nullptr;
+  if ((rc = static_scratch_base(device, &base, &num_cu))) return rc;
+  if (num_cu < 1 || num_cu * kMaxBlocksPerCU > kStaticMaxRows) return DPPF_ELIMIT;
+  // a plan-shaped view of the static scratch: nothing in it is owned, nothing is allocated
+  dppf_plan view;
+  view.M = M;
+  view.T = 1;
+  view.device = device;
+  view.num_cu = num_cu;
+  view.d = d;
+  view.nfull = static_cast<int>(d / kTileElems);
+  view.ntiles = view.nfull + (d % kTileElems ? 1 : 0);
+  view.tiles_dev = reinterpret_cast<Tile*>(base + kStaticOffTiles);
+  view.partials = reinterpret_cast<double*>(base + kStaticOffPartials);
+  view.partials_rows = kStaticMaxRows * kStaticMaxWorkers / M;
+  view.sched = reinterpret_cast<Sched*>(base + kStaticOffSched);
+  view.coef = reinterpret_cast<Coef*>(base + kStaticOffCoef);
+  const void** xd = reinterpret_cast<const void**>(base + kStaticOffPtrs);
+  // the tile list, the pointer table and a clean counter are written by a kernel (no copy from
+  // host memory, no memset: both would be foreign bodies in a captured graph)
+  int setup_blocks = (view.ntiles + kBlock - 1) / kBlock;
+  if (setup_blocks < 1) setup_blocks = 1;
+  if (setup_blocks > num_cu) setup_blocks = num_cu;
+  hipLaunchKernelGGL(k_flat_setup, dim3(setup_blocks), dim3(kBlock), 0, s, view.tiles_dev, static_cast<long long>(d),
+                     (float**)(xd), x, static_cast<long long>(ld), M, view.sched);
+  HIP_TRY(hipGetLastError());
+  if (view.ntiles == 0) return launch_finalize(&view, 0, pull, push, true, r_out, c_out, s);
+  GridShape shape;
+  if ((rc = launch_sweep1<false, 0, true>(&view, M, xd, nullptr, nullptr, nullptr, 0, 0, 0, 0, kKeepTail, &shape, s)))
+    return rc;
+  return launch_sweep2<0, false, true>(&view, M, xd, nullptr, nullptr, 0.f, 0, shape.nparts(), pull, push, r_out,
+                                       c_out, s);
 } DPPF_CATCH
 
 // ---- plain device-to-device copy of n floats with the library's own load/store path

@@ -1112,6 +1112,34 @@ __global__ __launch_bounds__(kBlock) void k_mean_any(const Tile* __restrict__ ti
       [](int) {});
 }
 
+// ------------------------------- work decomposition of ONE flat tensor, built on the device
+// For callers that may not allocate: the tile list of a single tensor of d elements per worker
+// (full tiles first, then the ragged tail, exactly what the host-side list builder produces) and
+// the table of the M workers' base pointers x + m*ld are written straight into caller-provided
+// device memory, and the on-demand counter is put back to zero.
+__global__ __launch_bounds__(kBlock) void k_flat_setup(Tile* __restrict__ tiles, long long d,
+                                                       float** __restrict__ ptrs, float* x, long long ld, int M,
+                                                       Sched* __restrict__ sched) {
+  const long long nfull = d / kTileElems;
+  const int tail = static_cast<int>(d - nfull * kTileElems);
+  const long long ntiles = nfull + (tail > 0 ? 1 : 0);
+  const long long stride = static_cast<long long>(gridDim.x) * kBlock;
+  for (long long t = static_cast<long long>(blockIdx.x) * kBlock + threadIdx.x; t < ntiles; t += stride) {
+    Tile tl;
+    tl.offset = t * kTileElems;
+    tl.tensor = 0;
+    tl.count = t < nfull ? kTileElems : tail;
+    tiles[t] = tl;
+  }
+  if (blockIdx.x == 0) {
+    if (static_cast<int>(threadIdx.x) < M) ptrs[threadIdx.x] = x + static_cast<long long>(threadIdx.x) * ld;
+    if (threadIdx.x == 0) {
+      sched->next = 0u;
+      sched->done = 0u;
+    }
+  }
+}
+
 // ---------------------------------------------- plain copy (bandwidth / counter calibration)
 __global__ __launch_bounds__(kBlock) void k_copy(float* __restrict__ dst, const float* __restrict__ src,
                                                  long long n) {

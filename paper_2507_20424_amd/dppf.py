@@ -54,6 +54,7 @@ def load():
         "dppf_pull_push_round_flat": (ctypes.c_int, [vp, vp, i64, f, f, vp, vp, vp, vp]),
         "dppf_local_sgd_step_flat": (ctypes.c_int, [vp, vp, vp, vp, i64, f, f, f, vp]),
         "dppf_round_flat": (ctypes.c_int, [vp, vp, vp, vp, i64, f, f, f, f, f, vp, vp, vp, vp]),
+        "dppf_pull_push_round_flat_static": (ctypes.c_int, [vp, ctypes.c_int, i64, i64, f, f, vp, vp, vp]),
         "dppf_pull_push_round_exact": (ctypes.c_int, [vp, c_fpp, f, f, vp, vp, vp]),
         "dppf_pull_then_push": (ctypes.c_int, [vp, c_fpp, c_fpp, f, f, ctypes.c_int, vp, vp]),
         "dppf_local_adamw_step": (ctypes.c_int, [vp, c_fpp, c_fpp, c_fpp, c_fpp, f, f, f, f, f, i64, vp]),
@@ -254,6 +255,13 @@ class Plan:
         n = self._lib.dppf_plan_timing_read(self._h, ids, ms, cap)
         _check(n, "dppf_plan_timing_read")
         return [(KERNEL_NAMES.get(ids[i], str(ids[i])), float(ms[i])) for i in range(n)]
+
+
+def pull_push_round_flat_static(x, M: int, d: int, ld: int, pull: float, push: float, r_out=None, c_out=None,
+                                stream=None) -> None:
+    """The plain round on one [M, ld] buffer without a plan and without any allocation."""
+    _check(load().dppf_pull_push_round_flat_static(_dev(x), M, d, ld, pull, push, _dev(r_out), _dev(c_out),
+                                                   _stream(stream)), "dppf_pull_push_round_flat_static")
 
 
 def util_copy(dst, src, n: int, stream=None) -> None:
