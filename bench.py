@@ -44,9 +44,11 @@ CALL_BYTES = {"round": 28.0, "pull_push": 12.0, "local_step": 20.0, "pull_push_e
 
 def kernel_source_hash() -> str:
     h = hashlib.sha256()
-    for name in ("dppf_kernels.h", "dppf.hip"):
-        with open(os.path.join(ROOT, "paper_2507_20424_amd", "csrc", name), "rb") as f:
-            h.update(f.read())
+    csrc = os.path.join(ROOT, "paper_2507_20424_amd", "csrc")
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".h", ".hip")):
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(f.read())
     return h.hexdigest()[:16]
 
 

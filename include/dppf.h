@@ -78,15 +78,18 @@ int dppf_plan_destroy(dppf_plan* plan);
 /* d = sum of numel. */
 int64_t dppf_plan_dim(const dppf_plan* plan);
 
-/* HOST-ONLY, needs no GPU: the work decomposition a plan would use for this tensor list.  Every
- * tensor is cut into tiles of at most DPPF_TILE_ELEMS consecutive elements; the list holds all
- * full tiles first (in list order), then the partial ones (tensor tails, small tensors).
- * Writes d = sum numel, the number of full tiles and the total; if the three tile arrays are
- * non-NULL (capacity `cap` entries, else DPPF_ELIMIT) also each tile's tensor index, first
- * element inside that tensor, and element count.  */
-#define DPPF_TILE_ELEMS 4096
-int dppf_layout_tiles(int T, const int64_t* numel, int64_t* d, int64_t* nfull, int64_t* ntiles, int64_t cap,
-                      int32_t* tile_tensor, int64_t* tile_offset, int32_t* tile_count);
+/* HOST-ONLY, need no GPU: the work decomposition.  Every tensor is cut into tiles of at most
+ * tile_elems consecutive elements; the list holds all full tiles first (in list order), then the
+ * partial ones (tensor tails, small tensors).  The sweeps of the round use tiles of
+ * dppf_sweep_tile_elems(M) elements (4096 up to 7 workers, 2048 up to 16, 1024 up to 39, 4096
+ * beyond); the local steps always use DPPF_STEP_TILE_ELEMS.  dppf_layout_tiles writes d = sum
+ * numel, the number of full tiles and the total; if the three tile arrays are non-NULL (capacity
+ * `cap` entries, else DPPF_ELIMIT) also each tile's tensor index, first element inside that
+ * tensor, and element count.  */
+#define DPPF_STEP_TILE_ELEMS 4096
+int dppf_sweep_tile_elems(int M);
+int dppf_layout_tiles(int tile_elems, int T, const int64_t* numel, int64_t* d, int64_t* nfull, int64_t* ntiles,
+                      int64_t cap, int32_t* tile_tensor, int64_t* tile_offset, int32_t* tile_count);
 
 /* ---------------------------------------------------------------------------------------
  * Steps of the round (Alg. 1 consensus branch with x_C = x_A; Sec. 5 Eq. 5).
@@ -133,9 +136,9 @@ int dppf_round(dppf_plan* plan, float* const* x, float* const* v, const float* c
  *   d_m = x_m - x_A;  x_m <- x_m - pull d_m + (push_r / M^2) (M d_m/||d_m|| - sum_j d_j/||d_j||).
  * push_r is the regulariser's own coefficient lambda_r (Eq. 5's lambda corresponds to push_r / M).
  * Workers at zero distance contribute a zero unit vector.  The average of the workers is
- * preserved.  r_out[m] = ||d_m||, c_out[m] = pull - (push_r/M)/r_m, both optional.  For M <= 16
- * the same two sweeps and the same memory traffic as dppf_pull_push_round; for more workers the
- * average and the sum of unit vectors are staged in two plan-owned d-vectors.  */
+ * preserved.  r_out[m] = ||d_m||, c_out[m] = pull - (push_r/M)/r_m, both optional.  Up to 39
+ * workers the same two sweeps and the same memory traffic as dppf_pull_push_round; for more workers
+ * the average and the sum of unit vectors are staged in two plan-owned d-vectors.  */
 int dppf_pull_push_round_exact(dppf_plan* plan, float* const* x, float pull, float push_r,
                                float* r_out, float* c_out, void* stream);
 
@@ -166,10 +169,21 @@ int dppf_round_adamw(dppf_plan* plan, float* const* x, float* const* m1, float* 
                      float weight_decay, int64_t step, float pull, float push, float* r_out,
                      float* c_out, void* stream);
 
+/* ||x_A||_2, the Euclidean norm of the workers' average (appendix "DPPF's Hyperparameter
+ * Sensitivity ..." tracks it next to the valley width): every round enqueued on a plan
+ * (dppf_pull_push_round, dppf_round, dppf_pull_push_round_exact, dppf_round_adamw) leaves the norm
+ * of the average it formed -- taken before the update, like r_out -- in the plan; this call
+ * enqueues a copy of it to out (DEVICE, 1 float).  It costs the round no extra memory traffic.  */
+int dppf_plan_average_norm(dppf_plan* plan, float* out, void* stream);
+
 /* What the paper logs every round (appendix "Pull-Push Mechanism"), from the distances r (device,
- * M floats, e.g. r_out of a round):  out[0] = relaxed MV = (1/M) sum_m r_m;
- * out[1..M] = pull strength pull*r_m;  out[M+1..2M] = push strength push.  out: device, 2M+1 floats. */
-int dppf_round_statistics(const float* r, int M, float pull, float push, float* out, void* stream);
+ * M floats, e.g. r_out of a round):  out[0] = relaxed MV = (1/M) sum_m r_m (the valley width);
+ * out[1..M] = pull strength pull*r_m;  out[M+1..2M] = push strength push.  With avg_norm (device,
+ * 1 float, e.g. from dppf_plan_average_norm; NULL to skip) also out[2M+1] = ||x_A|| and
+ * out[2M+2] = valley width / ||x_A|| (appendix, hyper-parameter sensitivity).
+ * out: device, 2M+3 floats.  */
+int dppf_round_statistics(const float* r, int M, float pull, float push, const float* avg_norm, float* out,
+                          void* stream);
 
 /* Push-strength schedules (appendix "How to Schedule The Pushing Force?"), a HOST function:
  * fixed: push;  decreasing: (push/2)(1 + cos(pi t/t_total));  increasing: (push/2)(1 - cos(pi t/t_total)). */
@@ -205,7 +219,7 @@ int dppf_round_flat(dppf_plan* plan, float* x, float* v, const float* g, int64_t
  * ------------------------------------------------------------------------------------- */
 #define DPPF_STATIC_MAX_WORKERS 16
 #define DPPF_STATIC_MAX_DIM 134217728            /* 2^27 elements per worker */
-#define DPPF_STATIC_SCRATCH_BYTES 787456
+#define DPPF_STATIC_SCRATCH_BYTES 1328384
 int dppf_pull_push_round_flat_static(float* x, int M, int64_t d, int64_t ld, float pull, float push,
                                      float* r_out, float* c_out, void* stream);
 
@@ -233,29 +247,6 @@ enum {
 };
 int dppf_plan_timing_enable(dppf_plan* plan, int enable);
 int dppf_plan_timing_read(dppf_plan* plan, int* kernel_id, float* ms, int cap);
-
-/* ---------------------------------------------------------------------------------------
- * Measurement aid, not part of the method: a plain copy dst[i] = src[i] of n floats (device
- * pointers, 4-byte aligned, non-overlapping) using the same 16-byte load/store path as the
- * kernels above.  It gives the practical bandwidth ceiling of the device and a launch of
- * known size (4n bytes read, 4n written) against which hardware counters can be scaled.
- * ------------------------------------------------------------------------------------- */
-int dppf_util_copy(float* dst, const float* src, int64_t n, void* stream);
-
-/* Measurement aid: streams `reads` arrays and writes `writes` arrays of n floats each; array k
- * starts at base + k*stride floats (base 16-byte aligned, stride >= n, multiple of 4).  Written
- * arrays are k = reads..reads+writes-1, or k = 0..writes-1 when inplace != 0 (the lane that read
- * an element overwrites it).  Only elements below the largest multiple of the probe's tile are
- * touched.  Supported (reads, writes): (1,0) (4,0) (12,0) (0,1) (0,4) (1,1) (2,1) and, with or without
- * inplace, (4,4) (8,4) (12,4) (12,8), and in place only (16,8) (24,8); anything else returns
- * DPPF_EINVAL.  blocks_per_cu in 1..16.  on_demand = 0: the blocks split the work evenly;
- * on_demand != 0: they take work on demand the way the library's read-write sweeps do (the second
- * half of it, or all of it when the launch moves more than about 2 GB).  The probe keeps one
- * counter per device: calls that could overlap on one device (different streams) must not both
- * use on_demand.
- * Timing is the caller's job (events around the call).  */
-int dppf_util_stream_probe(float* base, int64_t stride, int64_t n, int reads, int writes, int inplace,
-                           int blocks_per_cu, int on_demand, void* stream);
 
 #ifdef __cplusplus
 }

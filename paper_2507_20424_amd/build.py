@@ -8,20 +8,25 @@ import os
 import shutil
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
-SRC = os.path.join(PKG_DIR, "csrc", "dppf.hip")
-LIB = os.path.join(PKG_DIR, "csrc", "libdppf.so")
+CSRC = os.path.join(PKG_DIR, "csrc")
+# one translation unit per family of kernels, so that they compile side by side
+UNITS = ["dppf_api", "dppf_launch_reduce", "dppf_launch_step_reduce", "dppf_launch_update", "dppf_launch_seq",
+         "dppf_launch_adamw", "dppf_launch_misc", "dppf_launch_any", "dppf_launch_lds"]
+OBJ_DIR = os.path.join(CSRC, "_build")
+LIB = os.path.join(CSRC, "libdppf.so")
 CLI_SRC = os.path.join(PKG_DIR, "csrc", "dppf_cli.c")
 CLI = os.path.join(PKG_DIR, "csrc", "dppf_cli")
 INCLUDE = os.path.join(ROOT, "include")
 
 HIPCC_FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     # keep the compiler from forming packed-fp32 instructions out of scalar float code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-command-line-argument",
+    "-Wall", "-Wno-unused-command-line-argument", "-Wno-unused-function",
 ]
 
 
@@ -32,15 +37,34 @@ def hipcc_path() -> str:
     return exe
 
 
-def build_library(verbose: bool = True) -> str:
-    """Compile csrc/dppf.hip into csrc/libdppf.so (always recompiles)."""
-    cmd = [hipcc_path(), *HIPCC_FLAGS, "-I", INCLUDE, "-o", LIB + ".tmp", SRC]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout)
+        raise RuntimeError("command failed: " + " ".join(cmd) + "\n" + res.stdout)
+    return out
+
+
+def compile_unit(name: str, extra_flags=(), verbose: bool = True) -> str:
+    """hipcc -c one translation unit of csrc/ into csrc/_build/; returns the compiler's output."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    cmd = [hipcc_path(), *HIPCC_FLAGS, *extra_flags, "-I", INCLUDE, "-I", CSRC, "-c", "-o",
+           os.path.join(OBJ_DIR, name + ".o"), os.path.join(CSRC, name + ".hip")]
+    return _run(cmd, verbose)
+
+
+def build_library(verbose: bool = True, jobs: int = 8) -> str:
+    """Compile every unit of csrc/ (always recompiles) and link them into csrc/libdppf.so."""
+    with ThreadPoolExecutor(max_workers=max(1, min(jobs, len(UNITS)))) as pool:
+        outs = list(pool.map(lambda u: compile_unit(u, verbose=verbose), UNITS))
+    for out in outs:
+        if verbose and out.strip():
+            print(out)
+    objs = [os.path.join(OBJ_DIR, u + ".o") for u in UNITS]
+    out = _run([hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-Wno-unused-command-line-argument",
+                "-o", LIB + ".tmp", *objs], verbose)
     if verbose and out.strip():
         print(out)
     os.replace(LIB + ".tmp", LIB)

@@ -1,5 +1,13 @@
-// Device code of the DPPF library: tile walk, load/store helpers and every kernel.
-// Included once, by dppf.hip (which holds the plan, the launchers and the C ABI).
+// Device code of the DPPF library: load/store helpers and every kernel template.  Included by the
+// translation units that launch them (each instantiates only the kernels it launches).
+//
+// Three families of kernels cover the worker counts:
+//   * M <= 16: all M replicas of a lane's elements sit in registers (M is a template parameter);
+//   * 17 <= M <= 39: one 16-byte vector per lane and worker is staged in LDS (M is a run-time value;
+//     39 workers x 256 lanes x 16 bytes fill the CU's 160 KB), so the traffic stays at the algorithmic
+//     bytes;
+//   * any M: streaming kernels that read a STORED average instead of forming it (used beyond 39
+//     workers and by the variants that have no LDS form).
 #ifndef DPPF_KERNELS_H_
 #define DPPF_KERNELS_H_
 
@@ -7,34 +15,76 @@
 
 #include <type_traits>
 
-namespace {
+#include "dppf_walk.h"
 
+// Types and constants that the host side shares with the kernels.
+namespace dppf_detail {
+
+using dppf_walk::Sched;
+using dppf_walk::Tile;
+using dppf_walk::Walk;
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef f4 f4u __attribute__((aligned(4)));   // 16-byte vector that may sit on any 4-byte boundary
 
 constexpr int kBlock = 256;                   // threads per block (4 waves)
-constexpr int kTileElems = 4096;              // elements of ONE worker's tensor per tile (DPPF_TILE_ELEMS)
-constexpr int kVecPerThread = kTileElems / (4 * kBlock);   // 16-byte vectors per thread per tile
-constexpr int kMaxTemplM = 16;                 // worker counts with a register-resident kernel
-constexpr int kAnyChunk = 4;                   // workers whose loads the any-M kernels keep in flight together
-constexpr int kMaxBlocksPerCU = 8;             // upper bound on resident blocks per CU (sizes buffers)
+constexpr int kWaves = kBlock / 64;
+constexpr int kMaxTemplM = 16;                // worker counts with a register-resident kernel
+constexpr int kMaxLdsM = 39;                  // worker counts with an LDS-staged kernel
+constexpr int kAnyChunk = 4;                  // workers whose loads the any-M kernels keep in flight together
+constexpr int kMaxBlocksPerCU = 8;            // upper bound on resident blocks per CU (sizes buffers)
+
+// Elements of ONE worker's tensor per tile.  What a block holds of a tile grows with M, and from 8
+// workers on half-size tiles are faster (M = 8: +3 %, 12: +6 %, 16: +7 % on the fused round); below
+// that they are slower (M = 4: -4 %).  The LDS-staged kernels hold one vector per lane.  The
+// kernels that take one worker at a time and the any-M streaming kernels use kStepTileElems.
+constexpr int kStepTileElems = 4096;
+constexpr int kLdsTileElems = 4 * kBlock;
+constexpr int kSmallTileFromM = 8;
+constexpr int sweep_tile_elems(int M) {
+  return M < kSmallTileFromM ? 4096 : (M <= kMaxTemplM ? 2048 : (M <= kMaxLdsM ? kLdsTileElems : kStepTileElems));
+}
+constexpr int vectors_per_lane(int tile_elems) { return tile_elems / (4 * kBlock); }
+
 // Resident blocks per CU by traffic pattern (measured): kernels that mix reads and writes run
 // fastest with ONE block per CU -- fewer concurrently open DRAM rows and longer same-direction
 // bursts outweigh the lost latency hiding; kernels that only read do best with two.
 constexpr int kBlocksPerCUReadOnly = 2;
 constexpr int kBlocksPerCUReadWrite = 1;
-struct Tile {
-  long long offset;   // first element inside the tensor
-  int tensor;         // index into the tensor list
-  int count;          // 1..kTileElems elements
-};
 
 struct Coef {
   float c;            // alpha - lambda / r_m
   int skip;           // r_m == 0: leave the worker untouched
   float inv_r;        // 1 / r_m, 0 where r_m == 0
 };
+
+// Adam's hyper-parameters as the kernels take them: bc_i = 1 - beta_i^t is formed on the host.
+struct AdamHyper {
+  float lr, b1, b2, eps, wd, inv_bc1, inv_bc2;
+};
+
+// The kernels that handle one worker at a time (local steps) take two full tiles per item: one
+// tile of one worker is only about 3 microseconds of traffic, too little to hide the request for
+// the next item behind (measured: two tiles 3-6 % faster than one, three or four slower again;
+// the sweeps that take all workers of a tile together are fastest with one tile per item).
+constexpr int kTilesPerWorkerItem = 2;
+
+// What the LDS-staged first sweep folds in.  OPT: 0 = x as it is, 1 = momentum-SGD step (v stored,
+// stepped x kept only on chip), 2 = AdamW step (m1, m2 and the stepped x stored).
+constexpr int kLdsChunk = 4;                  // workers per register chunk of the LDS-staged kernels
+struct LdsOptArgs {
+  float* const* vp;          // SGD: momentum; AdamW: first moment
+  float* const* sp;          // AdamW: second moment
+  const float* const* gp;
+  float lr, mu, wd;          // SGD
+  AdamHyper adam;
+};
+
+}  // namespace dppf_detail
+
+namespace {
+
+using namespace dppf_detail;
 
 // ------------------------------------------------------------------------------- helpers
 // Tensor data always live in device (global) memory.  The pointers come out of pointer tables, so
@@ -74,6 +124,19 @@ template <bool FULL>
 __device__ __forceinline__ void store4_stream(float* p, f4 v, int n) {
   if (FULL || n >= 4) { __builtin_nontemporal_store(v, (gvec_out)(p)); return; }
   store4<false>(p, v, n);
+}
+
+// The first n components of v, zeros after them (n >= 4: v itself).  Lanes that reach past the end
+// of a partial tile compute on zeros; where a formula does not map zeros to zero (AdamW with
+// eps = 0 divides 0 by 0) its result is cut back before it enters a sum.
+template <bool FULL>
+__device__ __forceinline__ f4 first_components(f4 v, int n) {
+  if (FULL || n >= 4) return v;
+  f4 r = {0.f, 0.f, 0.f, 0.f};
+  if (n > 0) r.x = v.x;
+  if (n > 1) r.y = v.y;
+  if (n > 2) r.z = v.z;
+  return r;
 }
 
 __device__ __forceinline__ f4 fma4(f4 a, float b, f4 c) {
@@ -126,138 +189,111 @@ __device__ __forceinline__ double wave_sum(double v) {
   return v;
 }
 
-// Block-wide sums of M per-lane doubles; thread m < M writes the m-th sum to out[m].  The per-lane
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// Block-wide sums of C per-lane doubles; thread c < C writes the c-th sum to out[c].  The per-lane
 // values are set back to zero.  May be called repeatedly by a block, with at least one barrier
-// between two calls (the loop of walk_items has them).
-template <int M>
-__device__ __forceinline__ void block_sums_flush(double (&acc)[M], double* out) {
-  __shared__ double lds[kBlock / 64][M];
+// between two calls (the on-demand part of a walk has one per item).
+template <int C>
+__device__ __forceinline__ void block_sums_flush(double (&acc)[C], double* out) {
+  __shared__ double lds[kWaves][C];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
-  for (int m = 0; m < M; ++m) {
-    double s = wave_sum(acc[m]);
-    if (lane == 0) lds[wave][m] = s;
-    acc[m] = 0.0;
+  for (int c = 0; c < C; ++c) {
+    double s = wave_sum(acc[c]);
+    if (lane == 0) lds[wave][c] = s;
+    acc[c] = 0.0;
   }
   __syncthreads();
-  if (threadIdx.x < M) {
+  if (threadIdx.x < C) {
     double s = 0.0;
 #pragma unroll
-    for (int w = 0; w < kBlock / 64; ++w) s += lds[w][threadIdx.x];
+    for (int w = 0; w < kWaves; ++w) s += lds[w][threadIdx.x];
     out[threadIdx.x] = s;
   }
 }
 
-// The tile list holds all full tiles first, then the partial ones (tensor tails and tensors
-// smaller than a tile).  Blocks [0, gfull) take the full tiles, the remaining blocks the partial
-// ones, so a list of many small tensors does not put short, latency-bound tiles into the streaming
-// blocks' loops.
-//
-// Full tiles are work ITEMS (one per tile, or one per (two tiles, worker) pair).  Items [0, nstatic) go
-// to the blocks with a fixed stride; items [nstatic, count) are handed out on demand from a counter
-// in device memory.  The compute dies of the chip do not stream at the same rate (blocks on some
-// finish a fixed share about 10 % earlier than on others), and with a fixed split the early ones
-// idle while the late ones finish; handing out the tail on demand keeps every CU busy to the end.
-// The counter resets itself: the last block to leave puts it back to zero, so every launch finds
-// it clean and nothing has to be cleared between launches (also inside a captured graph).
-struct Sched {
-  unsigned int next;   // next on-demand item to hand out
-  unsigned int done;   // full-tile blocks that have left the kernel
-};
-
-struct Walk {
-  int nfull, ntiles;   // tiles [0, nfull) are full, [nfull, ntiles) partial
-  int gfull;           // blocks [0, gfull) take full tiles
-  int nitems;          // full-tile work items: one per tile, or one per (pair of tiles, worker)
-  int nstatic;         // full-tile items with a fixed owner; the rest are handed out on demand
-  Sched* sched;        // used only when nstatic < nitems
-};
-
-// The kernels that handle one worker at a time (local steps) take two full tiles per item: one
-// tile of one worker is only about 3 microseconds of traffic, too little to hide the request for
-// the next item behind (measured: two tiles 3-6 % faster than one, three or four slower again;
-// the sweeps that take all workers of a tile together are fastest with one tile per item).
-constexpr int kTilesPerWorkerItem = 2;
-
-using FullTile = std::integral_constant<bool, true>;
-using PartialTile = std::integral_constant<bool, false>;
-
-// Calls body(item, FullTile{} or PartialTile{}) for every item of this block, all threads of the
-// block together.  item counts within the full tiles or within the partial tiles.  A block owns
-// the items congruent to its index (modulo the number of blocks on that part of the list) in the
-// forward and in the REVERSE walk alike, so on a small model sweep 2 finds in its die's L2 what
-// sweep 1 left there.  REVERSE walks from the far end: the fixed shares are the upper items and the
-// on-demand ones run down to item 0, so sweep 2 starts where sweep 1 stopped, whose data are still
-// in the last-level cache.  flush(row) is called with row = blockIdx.x once the block's fixed share
-// (or its partial tiles) is done, and with row = gridDim.x + k after the k-th on-demand item:
-// kernels that reduce store their partial sums there, so that the set of rows and what each row
-// holds never depend on which block took which item -- results stay bit-reproducible.
-template <bool REVERSE, typename Body, typename Flush>
-__device__ __forceinline__ void walk_items(const Walk& w, int per_tile, Body&& body, Flush&& flush) {
-  __shared__ int s_next[2];
-  const bool full = static_cast<int>(blockIdx.x) < w.gfull;
-  const int me = full ? static_cast<int>(blockIdx.x) : static_cast<int>(blockIdx.x) - w.gfull;
-  const int lanes = full ? w.gfull : static_cast<int>(gridDim.x) - w.gfull;
-  const int count = full ? w.nitems : (w.ntiles - w.nfull) * per_tile;
-  // last item this block owns (below `me` if it owns none)
-  const int last_owned = count > me ? me + ((count - 1 - me) / lanes) * lanes : me - lanes;
-  if (!full) {
-    if (REVERSE) {
-      for (int j = last_owned; j >= me; j -= lanes) body(j, PartialTile{});
-    } else {
-      for (int j = me; j < count; j += lanes) body(j, PartialTile{});
-    }
-    flush(static_cast<int>(blockIdx.x));
-    return;
+// The same for a run-time number of columns: per-wave running sums in LDS (`acc`, kWaves x cols
+// doubles, the caller's memory).  add() folds one value per lane into column `col` -- all lanes of
+// a wave must call it together; flush() writes the block's sums and clears them.
+struct ColumnSums {
+  double* acc;
+  int cols;
+  __device__ __forceinline__ void init(double* lds, int ncols) {
+    acc = lds;
+    cols = ncols;
+    for (int i = threadIdx.x; i < kWaves * cols; i += kBlock) acc[i] = 0.0;
+    __syncthreads();
   }
-  const int ndyn = count - w.nstatic;            // items handed out on demand
-  const int lo = REVERSE ? ndyn : 0;             // fixed shares are the items [lo, lo + nstatic)
-  // The first on-demand item is requested right away: the answer is there long before it is needed.
-  unsigned int fetched = 0;
-  if (ndyn > 0 && threadIdx.x == 0) fetched = atomicAdd(&w.sched->next, 1u);
-  int j = REVERSE ? last_owned : me;
-  bool on_demand = false;
+  __device__ __forceinline__ void add(float v, int col) {
+    const float s = wave_sum(v);
+    if ((threadIdx.x & 63) == 0) acc[(threadIdx.x >> 6) * cols + col] += static_cast<double>(s);
+  }
+  __device__ __forceinline__ void flush(double* out) {
+    __syncthreads();
+    for (int c = threadIdx.x; c < cols; c += kBlock) {
+      double s = 0.0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        s += acc[w * cols + c];
+        acc[w * cols + c] = 0.0;
+      }
+      out[c] = s;
+    }
+    __syncthreads();
+  }
+};
+
+// A thread block's view of the machine for dppf_walk::walk_items.
+struct BlockEnv {
   int slot = 0;   // the item number travels from thread 0 to the block through two alternating words:
                   // one barrier per item is enough, the next write goes to the other word
-  for (;;) {
-    if (!on_demand && (REVERSE ? j < lo : j >= lo + w.nstatic)) {
-      flush(static_cast<int>(blockIdx.x));
-      if (ndyn <= 0) break;
-      on_demand = true;
-    }
-    int k = 0;
-    if (on_demand) {
-      if (threadIdx.x == 0) s_next[slot] = static_cast<int>(fetched);
-      __syncthreads();
-      k = s_next[slot];
-      slot ^= 1;
-      if (k >= ndyn) break;            // every block gets here: the counter only grows
-      if (threadIdx.x == 0) fetched = atomicAdd(&w.sched->next, 1u);   // the one after, while this one runs
-      j = REVERSE ? ndyn - 1 - k : w.nstatic + k;
-    }
-    body(j, FullTile{});
-    if (on_demand) flush(static_cast<int>(gridDim.x) + k);
-    else j += REVERSE ? -lanes : lanes;
+  __device__ __forceinline__ int block() const { return static_cast<int>(blockIdx.x); }
+  __device__ __forceinline__ int grid() const { return static_cast<int>(gridDim.x); }
+  __device__ __forceinline__ unsigned int request(Sched* s) {
+    return threadIdx.x == 0 ? atomicAdd(&s->next, 1u) : 0u;
   }
-  // A block counts itself out only after its last request has been answered, so when the count is
-  // complete nobody will touch the counter again in this launch.
-  if (ndyn > 0 && threadIdx.x == 0 &&
-      atomicAdd(&w.sched->done, 1u) == static_cast<unsigned int>(w.gfull) - 1u) {
-    atomicExch(&w.sched->next, 0u);
-    atomicExch(&w.sched->done, 0u);
+  __device__ __forceinline__ int share(unsigned int v) {
+    __shared__ int s_next[2];
+    if (threadIdx.x == 0) s_next[slot] = static_cast<int>(v);
+    __syncthreads();
+    const int k = s_next[slot];
+    slot ^= 1;
+    return k;
   }
+  __device__ __forceinline__ void leave(Sched* s, int gfull) {
+    if (threadIdx.x == 0 && atomicAdd(&s->done, 1u) == static_cast<unsigned int>(gfull) - 1u) {
+      atomicExch(&s->next, 0u);
+      atomicExch(&s->done, 0u);
+    }
+  }
+};
+
+template <bool REVERSE, typename FullBody, typename PartBody, typename Flush>
+__device__ __forceinline__ void walk(const Walk& w, int per_tile, FullBody&& full_body, PartBody&& part_body,
+                                     Flush&& flush) {
+  BlockEnv env;
+  dppf_walk::walk_items<REVERSE>(env, w, per_tile, full_body, part_body, flush);
 }
 
+// ===================================================================== M <= 16: in registers
 // --------------------------------------------------------------------- sweep 1 of the round
-// XBAR: 0 = average stays in registers, 1 = also written out, 2 = read from memory instead of
-// being recomputed (dppf_dist_norms with a given x_A).
+// XBAR: 0 = average stays in registers, 1 = also written out.
 // KEEPX: load x through the caches (it is read again soon) instead of streaming it past them.
+// acc[0..M-1]: squared distances; acc[M]: squared norm of the average (the appendix section on
+// hyper-parameter sensitivity tracks ||x_A||; it rides along for four multiply-adds per vector).
 template <int M, int U, bool SGD, int XBAR, bool NORMS, bool FULL, bool KEEPX>
 __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* __restrict__ xp,
                                             float* const* __restrict__ vp,
                                             const float* const* __restrict__ gp,
                                             float* const* __restrict__ xbarp, float lr, float mu,
-                                            float wd, float inv_m, double (&acc)[M]) {
+                                            float wd, float inv_m, double (&acc)[M + 1]) {
+  constexpr int kVec = vectors_per_lane(sweep_tile_elems(M));
+  static_assert(kVec % U == 0, "a lane's vectors of a tile are taken U at a time");
   float* x[M];
   float* v[M];
   const float* g[M];
@@ -271,16 +307,16 @@ __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* 
   }
   float* xb = (XBAR != 0) ? xbarp[tl.tensor] + tl.offset : nullptr;
 
-  float part[M];
+  float part[M + 1];
 #pragma unroll
-  for (int m = 0; m < M; ++m) part[m] = 0.f;
+  for (int m = 0; m <= M; ++m) part[m] = 0.f;
 
   // One worker at a time: all U vectors of worker m are loaded (and, with the step, updated and
   // their momentum stored) before worker m+1 is touched, so a wave's burst of memory traffic
   // stays on a few streams instead of spreading over all M workers' -- measured 4 % faster than
   // vector-by-vector over all workers.
 #pragma unroll 1
-  for (int it = 0; it < kVecPerThread / U; ++it) {
+  for (int it = 0; it < kVec / U; ++it) {
     int e[U], n[U];
 #pragma unroll
     for (int k = 0; k < U; ++k) {
@@ -319,25 +355,19 @@ __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* 
     }
 #pragma unroll
     for (int k = 0; k < U; ++k) {
-      if (XBAR == 2) {
-        const f4 xbar = load4<FULL>(xb + e[k], n[k]);
-        if (NORMS) {
+      const f4 mo = mean_offset<M>(xv[k], inv_m);
+      const f4 xa = xv[k][0] + mo;
+      if (XBAR == 1) store4_stream<FULL>(xb + e[k], xa, n[k]);
+      if (NORMS) {
 #pragma unroll
-          for (int m = 0; m < M; ++m) part[m] = sumsq4(xv[k][m] - xbar, part[m]);
-        }
-      } else {
-        const f4 mu = mean_offset<M>(xv[k], inv_m);
-        if (XBAR == 1) store4_stream<FULL>(xb + e[k], xv[k][0] + mu, n[k]);
-        if (NORMS) {
-#pragma unroll
-          for (int m = 0; m < M; ++m) part[m] = sumsq4((xv[k][m] - xv[k][0]) - mu, part[m]);
-        }
+        for (int m = 0; m < M; ++m) part[m] = sumsq4((xv[k][m] - xv[k][0]) - mo, part[m]);
+        part[M] = sumsq4(xa, part[M]);
       }
     }
   }
   if (NORMS) {
 #pragma unroll
-    for (int m = 0; m < M; ++m) acc[m] += static_cast<double>(part[m]);
+    for (int m = 0; m <= M; ++m) acc[m] += static_cast<double>(part[m]);
   }
 }
 
@@ -349,42 +379,42 @@ __global__ __launch_bounds__(kBlock) void k_sweep1(const Tile* __restrict__ tile
                                                    float* const* __restrict__ xbarp, float lr,
                                                    float mu, float wd, double* __restrict__ partials,
                                                    int pstride, int keep_from) {
-  double acc[M];
+  double acc[M + 1];
 #pragma unroll
-  for (int m = 0; m < M; ++m) acc[m] = 0.0;
+  for (int m = 0; m <= M; ++m) acc[m] = 0.0;
   const float inv_m = 1.0f / static_cast<float>(M);
-  walk_items<false>(
+  walk<false>(
       w, 1,
-      [&](int t, auto full) {
-        if constexpr (decltype(full)::value) {
-          // Pure reads stream fastest when they bypass the last-level cache, but the tiles this sweep
-          // touches last are the ones sweep 2 (which walks backwards) reads first: those, from
-          // keep_from on, go through the cache so that sweep 2 finds them there.
-          if (t < keep_from) {
-            sweep1_tile<M, U, SGD, XBAR, NORMS, true, false>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
-          } else {
-            // The two branches differ only in the cache hint of their loads; left alone the compiler
-            // merges them and drops the hint.  The empty statements keep them apart.
-            asm volatile("" ::: "memory");
-            sweep1_tile<M, U, SGD, XBAR, NORMS, true, true>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
-            asm volatile("" ::: "memory");
-          }
+      [&](int t) {
+        // Pure reads stream fastest when they bypass the last-level cache, but the tiles this sweep
+        // touches last are the ones sweep 2 (which walks backwards) reads first: those, from
+        // keep_from on, go through the cache so that sweep 2 finds them there.
+        if (t < keep_from) {
+          sweep1_tile<M, U, SGD, XBAR, NORMS, true, false>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
         } else {
-          sweep1_tile<M, U, SGD, XBAR, NORMS, false, true>(tiles[w.nfull + t], T, xp, vp, gp, xbarp, lr, mu, wd,
-                                                           inv_m, acc);
+          // The two branches differ only in the cache hint of their loads; left alone the compiler
+          // merges them and drops the hint.  The empty statements keep them apart.
+          asm volatile("" ::: "memory");
+          sweep1_tile<M, U, SGD, XBAR, NORMS, true, true>(tiles[t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m, acc);
+          asm volatile("" ::: "memory");
         }
       },
+      [&](int t) {
+        sweep1_tile<M, U, SGD, XBAR, NORMS, false, true>(tiles[w.nfull + t], T, xp, vp, gp, xbarp, lr, mu, wd, inv_m,
+                                                         acc);
+      },
       [&](int row) {
-        if (NORMS) block_sums_flush<M>(acc, partials + static_cast<size_t>(row) * pstride);
+        if (NORMS) block_sums_flush<M + 1>(acc, partials + static_cast<size_t>(row) * pstride);
       });
 }
 
 // ------------------------------------------------------- partial sums -> r_m and c_m (Eq. 5)
-// One block per worker; fixed summation order, fp64.
+// One block per column of the partial sums; fixed summation order, fp64.  Columns 0..M-1 are the
+// workers' squared distances, column M is the squared norm of the average.
 __global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ partials, int nparts,
-                                                     int pstride, float pull, float push,
+                                                     int pstride, int M, float pull, float push,
                                                      Coef* __restrict__ coef, float* __restrict__ r_out,
-                                                     float* __restrict__ c_out) {
+                                                     float* __restrict__ c_out, float* __restrict__ avg_norm_out) {
   __shared__ double lds[kBlock];
   const int m = blockIdx.x;
   double s = 0.0;
@@ -397,6 +427,10 @@ __global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ 
   }
   if (threadIdx.x == 0) {
     const double r = sqrt(lds[0]);
+    if (m == M) {
+      if (avg_norm_out) avg_norm_out[0] = static_cast<float>(r);
+      return;
+    }
     const bool zero = !(r > 0.0);
     // a worker sitting exactly on the average has no push direction: coefficient alpha, no move
     const double c = zero ? static_cast<double>(pull)
@@ -419,39 +453,46 @@ __device__ __forceinline__ void coefficients_from_partials(const double* __restr
                                                            float (&c)[M], bool (&skip)[M],
                                                            float (&inv_r)[M],
                                                            float* __restrict__ r_out,
-                                                           float* __restrict__ c_out) {
-  __shared__ double lds[kBlock / 64][M];
+                                                           float* __restrict__ c_out,
+                                                           float* __restrict__ avg_norm_out) {
+  __shared__ double lds[kWaves][M + 1];
   __shared__ float c_sh[M];
   __shared__ float inv_sh[M];
   __shared__ int skip_sh[M];
-  double acc[M];
+  const bool want_avg = blockIdx.x == 0 && avg_norm_out != nullptr;   // only one block needs column M
+  double acc[M + 1];
 #pragma unroll
-  for (int m = 0; m < M; ++m) acc[m] = 0.0;
+  for (int m = 0; m <= M; ++m) acc[m] = 0.0;
   for (int b = threadIdx.x; b < nparts; b += kBlock) {
 #pragma unroll
     for (int m = 0; m < M; ++m) acc[m] += partials[static_cast<size_t>(b) * pstride + m];
+    if (want_avg) acc[M] += partials[static_cast<size_t>(b) * pstride + M];
   }
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
-  for (int m = 0; m < M; ++m) {
+  for (int m = 0; m <= M; ++m) {
     const double s = wave_sum(acc[m]);
     if (lane == 0) lds[wave][m] = s;
   }
   __syncthreads();
-  if (threadIdx.x < M) {
+  if (threadIdx.x <= M) {
     double s = 0.0;
 #pragma unroll
-    for (int w = 0; w < kBlock / 64; ++w) s += lds[w][threadIdx.x];
+    for (int w = 0; w < kWaves; ++w) s += lds[w][threadIdx.x];
     const double r = sqrt(s);
-    const bool zero = !(r > 0.0);
-    const double cc = zero ? static_cast<double>(pull)
-                           : static_cast<double>(pull) - static_cast<double>(push) / r;
-    c_sh[threadIdx.x] = static_cast<float>(cc);
-    inv_sh[threadIdx.x] = zero ? 0.f : static_cast<float>(1.0 / r);
-    skip_sh[threadIdx.x] = zero ? 1 : 0;
-    if (blockIdx.x == 0) {
-      if (r_out) r_out[threadIdx.x] = static_cast<float>(r);
-      if (c_out) c_out[threadIdx.x] = static_cast<float>(cc);
+    if (threadIdx.x == M) {
+      if (want_avg) avg_norm_out[0] = static_cast<float>(r);
+    } else {
+      const bool zero = !(r > 0.0);
+      const double cc = zero ? static_cast<double>(pull)
+                             : static_cast<double>(pull) - static_cast<double>(push) / r;
+      c_sh[threadIdx.x] = static_cast<float>(cc);
+      inv_sh[threadIdx.x] = zero ? 0.f : static_cast<float>(1.0 / r);
+      skip_sh[threadIdx.x] = zero ? 1 : 0;
+      if (blockIdx.x == 0) {
+        if (r_out) r_out[threadIdx.x] = static_cast<float>(r);
+        if (c_out) c_out[threadIdx.x] = static_cast<float>(cc);
+      }
     }
   }
   __syncthreads();
@@ -464,15 +505,15 @@ __device__ __forceinline__ void coefficients_from_partials(const double* __restr
 }
 
 // --------------------------------------------------------------------- sweep 2 of the round
-// Eq. 5: x_m <- x_m + (x_A - x_m) c_m, with x_A recomputed from the same M loads (XBAR == 0)
-// or read from memory (XBAR == 2).
+// Eq. 5: x_m <- x_m + (x_A - x_m) c_m, with x_A recomputed from the same M loads.
 // STEP: x in memory is still the value from before the fused local step and v is already the
 // new momentum; the stepped x is rebuilt as x - lr v before the update.
-template <int M, int U, int XBAR, bool STEP, bool FULL>
+template <int M, int U, bool STEP, bool FULL>
 __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* __restrict__ xp,
-                                            const float* const* __restrict__ vp,
-                                            const float* const* __restrict__ xbarp, float lr,
+                                            const float* const* __restrict__ vp, float lr,
                                             const float (&c)[M], unsigned int skip, float inv_m) {
+  constexpr int kVec = vectors_per_lane(sweep_tile_elems(M));
+  static_assert(kVec % U == 0, "a lane's vectors of a tile are taken U at a time");
   float* x[M];
   const float* v[M];
 #pragma unroll
@@ -480,9 +521,8 @@ __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* 
     x[m] = xp[m * T + tl.tensor] + tl.offset;
     if (STEP) v[m] = vp[m * T + tl.tensor] + tl.offset;
   }
-  const float* xb = (XBAR == 2) ? xbarp[tl.tensor] + tl.offset : nullptr;
 #pragma unroll 1
-  for (int it = 0; it < kVecPerThread / U; ++it) {
+  for (int it = 0; it < kVec / U; ++it) {
     int e[U], n[U];
     f4 xv[U][M];
 #pragma unroll
@@ -503,19 +543,15 @@ __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* 
         for (int k = 0; k < U; ++k) xv[k][m] = fma4(vv[k], -lr, xv[k][m]);
       }
     }
-    // ref - (x_m - base) is the gap x_A - x_m: base = 0, ref = x_A when the average is given,
-    // base = x_0, ref = mu otherwise
-    f4 ref[U], base[U];
+    // mu - (x_m - x_0) is the gap x_A - x_m
+    f4 mo[U];
 #pragma unroll
-    for (int k = 0; k < U; ++k) {
-      ref[k] = (XBAR == 2) ? load4_stream<FULL>(xb + e[k], n[k]) : mean_offset<M>(xv[k], inv_m);
-      base[k] = (XBAR == 2) ? (f4){0.f, 0.f, 0.f, 0.f} : xv[k][0];
-    }
+    for (int k = 0; k < U; ++k) mo[k] = mean_offset<M>(xv[k], inv_m);
 #pragma unroll
     for (int m = 0; m < M; ++m) {
 #pragma unroll
       for (int k = 0; k < U; ++k) {
-        const f4 moved = fma4(ref[k] - (xv[k][m] - base[k]), c[m], xv[k][m]);
+        const f4 moved = fma4(mo[k] - (xv[k][m] - xv[k][0]), c[m], xv[k][m]);
         store4_stream<FULL>(x[m] + e[k], ((skip >> m) & 1u) ? xv[k][m] : moved, n[k]);
       }
     }
@@ -524,21 +560,22 @@ __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* 
 
 // FOLD: the coefficients are derived here from sweep 1's partial sums (no finalize launch);
 // otherwise they are read from `coef`.
-template <int M, int U, int XBAR, bool STEP, bool FOLD>
+template <int M, int U, bool STEP, bool FOLD>
 __global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tiles, const Walk w, int T,
                                                    float* const* __restrict__ xp,
-                                                   const float* const* __restrict__ vp,
-                                                   const float* const* __restrict__ xbarp, float lr,
-                                                   const Coef* __restrict__ coef, float inv_m_total,
+                                                   const float* const* __restrict__ vp, float lr,
+                                                   const Coef* __restrict__ coef,
                                                    const double* __restrict__ partials, int nparts,
                                                    int pstride, float pull, float push,
-                                                   float* __restrict__ r_out, float* __restrict__ c_out) {
+                                                   float* __restrict__ r_out, float* __restrict__ c_out,
+                                                   float* __restrict__ avg_norm_out) {
   float c[M];
   unsigned int skip = 0;        // bit m: worker m sits on the average and stays where it is
   if (FOLD) {
     float inv_r[M];
     bool on_average[M];
-    coefficients_from_partials<M>(partials, nparts, pstride, pull, push, c, on_average, inv_r, r_out, c_out);
+    coefficients_from_partials<M>(partials, nparts, pstride, pull, push, c, on_average, inv_r, r_out, c_out,
+                                  avg_norm_out);
 #pragma unroll
     for (int m = 0; m < M; ++m) skip |= on_average[m] ? (1u << m) : 0u;
   } else {
@@ -548,14 +585,10 @@ __global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tile
       skip |= coef[m].skip != 0 ? (1u << m) : 0u;
     }
   }
-  walk_items<true>(
-      w, 1,
-      [&](int t, auto full) {
-        if constexpr (decltype(full)::value)
-          sweep2_tile<M, U, XBAR, STEP, true>(tiles[t], T, xp, vp, xbarp, lr, c, skip, inv_m_total);
-        else
-          sweep2_tile<M, U, XBAR, STEP, false>(tiles[w.nfull + t], T, xp, vp, xbarp, lr, c, skip, inv_m_total);
-      },
+  const float inv_m = 1.0f / static_cast<float>(M);
+  walk<true>(
+      w, 1, [&](int t) { sweep2_tile<M, U, STEP, true>(tiles[t], T, xp, vp, lr, c, skip, inv_m); },
+      [&](int t) { sweep2_tile<M, U, STEP, false>(tiles[w.nfull + t], T, xp, vp, lr, c, skip, inv_m); },
       [](int) {});
 }
 
@@ -568,11 +601,13 @@ template <int M, int U, bool FULL>
 __device__ __forceinline__ void exact_tile(const Tile tl, int T, float* const* __restrict__ xp,
                                            const float (&c)[M], const float (&inv_r)[M], float k2,
                                            float inv_m) {
+  constexpr int kVec = vectors_per_lane(sweep_tile_elems(M));
+  static_assert(kVec % U == 0, "a lane's vectors of a tile are taken U at a time");
   float* x[M];
 #pragma unroll
   for (int m = 0; m < M; ++m) x[m] = xp[m * T + tl.tensor] + tl.offset;
 #pragma unroll 1
-  for (int it = 0; it < kVecPerThread / U; ++it) {
+  for (int it = 0; it < kVec / U; ++it) {
     int e[U], n[U];
     f4 xv[U][M];
 #pragma unroll
@@ -609,141 +644,38 @@ __global__ __launch_bounds__(kBlock) void k_update_exact(const Tile* __restrict_
                                                          float* const* __restrict__ xp,
                                                          const double* __restrict__ partials, int nparts,
                                                          int pstride, float pull, float push_over_m, float k2,
-                                                         float* __restrict__ r_out, float* __restrict__ c_out) {
+                                                         float* __restrict__ r_out, float* __restrict__ c_out,
+                                                         float* __restrict__ avg_norm_out) {
   float c[M], inv_r[M];
   bool skip[M];
-  coefficients_from_partials<M>(partials, nparts, pstride, pull, push_over_m, c, skip, inv_r, r_out, c_out);
+  coefficients_from_partials<M>(partials, nparts, pstride, pull, push_over_m, c, skip, inv_r, r_out, c_out,
+                                avg_norm_out);
   const float inv_m = 1.0f / static_cast<float>(M);
-  walk_items<true>(
-      w, 1,
-      [&](int t, auto full) {
-        if constexpr (decltype(full)::value) exact_tile<M, U, true>(tiles[t], T, xp, c, inv_r, k2, inv_m);
-        else exact_tile<M, U, false>(tiles[w.nfull + t], T, xp, c, inv_r, k2, inv_m);
-      },
-      [](int) {});
-}
-
-// ---- the exact update when there are more workers than fit in registers: the sum of unit gap
-// vectors S = sum_j (x_A - x_j) / r_j is materialised once (any M), then every group of up to
-// kMaxTemplM workers applies  x_m + (x_A - x_m) c_m + k2 S  with x_A and S read from memory.
-template <bool FULL>
-__device__ __forceinline__ void unit_sum_tile(const Tile tl, int M, int T, float* const* __restrict__ xp,
-                                              const float* xb, const Coef* __restrict__ coef, float* out) {
-  // Same chunked loads as the any-M average; the sum runs over the workers in ascending order.
-  f4 xbar[kVecPerThread], s[kVecPerThread];
-#pragma unroll
-  for (int it = 0; it < kVecPerThread; ++it) {
-    const int e = 4 * (threadIdx.x + it * kBlock);
-    xbar[it] = load4<FULL>(xb + e, FULL ? 4 : tl.count - e);
-    s[it] = (f4){0.f, 0.f, 0.f, 0.f};
-  }
-#pragma unroll 1
-  for (int m = 0; m < M; m += kAnyChunk) {
-    f4 t[kAnyChunk][kVecPerThread];
-    float w[kAnyChunk];
-#pragma unroll
-    for (int k = 0; k < kAnyChunk; ++k)
-      if (m + k < M) {
-        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
-        w[k] = coef[m + k].inv_r;
-#pragma unroll
-        for (int it = 0; it < kVecPerThread; ++it) {
-          const int e = 4 * (threadIdx.x + it * kBlock);
-          t[k][it] = load4<FULL>(base + e, FULL ? 4 : tl.count - e);
-        }
-      }
-#pragma unroll
-    for (int k = 0; k < kAnyChunk; ++k)
-      if (m + k < M) {
-#pragma unroll
-        for (int it = 0; it < kVecPerThread; ++it) s[it] = fma4(xbar[it] - t[k][it], w[k], s[it]);
-      }
-  }
-#pragma unroll
-  for (int it = 0; it < kVecPerThread; ++it) {
-    const int e = 4 * (threadIdx.x + it * kBlock);
-    store4<FULL>(out + e, s[it], FULL ? 4 : tl.count - e);
-  }
-}
-
-__global__ __launch_bounds__(kBlock) void k_unit_sum_any(const Tile* __restrict__ tiles, const Walk w, int M, int T,
-                                                         float* const* __restrict__ xp,
-                                                         const float* const* __restrict__ xbarp,
-                                                         const Coef* __restrict__ coef,
-                                                         float* const* __restrict__ sump) {
-  walk_items<false>(
-      w, 1,
-      [&](int t, auto full) {
-        constexpr bool kFull = decltype(full)::value;
-        const Tile tl = tiles[kFull ? t : w.nfull + t];
-        unit_sum_tile<kFull>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset, coef, sump[tl.tensor] + tl.offset);
-      },
-      [](int) {});
-}
-
-template <int M, int U, bool FULL>
-__device__ __forceinline__ void exact_given_tile(const Tile tl, int T, float* const* __restrict__ xp,
-                                                 const float* xb, const float* us, const float (&c)[M], float k2) {
-#pragma unroll 1
-  for (int it = 0; it < kVecPerThread / U; ++it) {
-#pragma unroll
-    for (int k = 0; k < U; ++k) {
-      const int e = 4 * (threadIdx.x + (it * U + k) * kBlock);
-      const int n = FULL ? 4 : tl.count - e;
-      const f4 xbar = load4_stream<FULL>(xb + e, n);
-      const f4 usum = load4_stream<FULL>(us + e, n);
-#pragma unroll
-      for (int m = 0; m < M; ++m) {
-        float* x = xp[m * T + tl.tensor] + tl.offset + e;
-        const f4 xv = load4_stream<FULL>(x, n);
-        f4 moved = fma4(xbar - xv, c[m], xv);
-        moved = fma4(usum, k2, moved);
-        store4_stream<FULL>(x, moved, n);
-      }
-    }
-  }
-}
-
-template <int M, int U>
-__global__ __launch_bounds__(kBlock) void k_update_exact_given(const Tile* __restrict__ tiles, const Walk w, int T,
-                                                               float* const* __restrict__ xp,
-                                                               const float* const* __restrict__ xbarp,
-                                                               const float* const* __restrict__ sump,
-                                                               const Coef* __restrict__ coef, float k2) {
-  float c[M];
-#pragma unroll
-  for (int m = 0; m < M; ++m) c[m] = coef[m].c;
-  walk_items<false>(
-      w, 1,
-      [&](int t, auto full) {
-        constexpr bool kFull = decltype(full)::value;
-        const Tile tl = tiles[kFull ? t : w.nfull + t];
-        exact_given_tile<M, U, kFull>(tl, T, xp, xbarp[tl.tensor] + tl.offset, sump[tl.tensor] + tl.offset, c, k2);
-      },
-      [](int) {});
+  walk<true>(
+      w, 1, [&](int t) { exact_tile<M, U, true>(tiles[t], T, xp, c, inv_r, k2, inv_m); },
+      [&](int t) { exact_tile<M, U, false>(tiles[w.nfull + t], T, xp, c, inv_r, k2, inv_m); }, [](int) {});
 }
 
 // ------------------------------------------- Alg. 1 written literally, any consensus variable
 // pulled_m = (1 - alpha) x_m + alpha x_C; gap_m = pulled_m - ref (ref = x_A before the round, or x_C);
 // r_m = ||gap_m||; x_m <- pulled_m + lambda gap_m / r_m  (no push where r_m = 0).
 // REF: 0 = push away from the average (formed from these M workers), 1 = push away from the
-// consensus variable, 2 = push away from an average that is read from memory (when the kernel
-// sees only a group of the workers).
+// consensus variable.
 template <int M, int U, int REF, bool WRITE, bool FULL>
 __device__ __forceinline__ void seq_tile(const Tile tl, int T, float* const* __restrict__ xp,
-                                         const float* const* __restrict__ xcp,
-                                         const float* const* __restrict__ refp, float pull, float keep,
-                                         const float (&scale)[M], float inv_m, double (&acc)[M]) {
+                                         const float* const* __restrict__ xcp, float pull, float keep,
+                                         const float (&scale)[M], float inv_m, double (&acc)[M + 1]) {
+  constexpr int kVec = vectors_per_lane(sweep_tile_elems(M));
+  static_assert(kVec % U == 0, "a lane's vectors of a tile are taken U at a time");
   float* x[M];
 #pragma unroll
   for (int m = 0; m < M; ++m) x[m] = xp[m * T + tl.tensor] + tl.offset;
   const float* xc = xcp[tl.tensor] + tl.offset;
-  const float* rf = (REF == 2) ? refp[tl.tensor] + tl.offset : nullptr;
   float part[M];
 #pragma unroll
   for (int m = 0; m < M; ++m) part[m] = 0.f;
 #pragma unroll 1
-  for (int it = 0; it < kVecPerThread / U; ++it) {
+  for (int it = 0; it < kVec / U; ++it) {
     int e[U], n[U];
     f4 xv[U][M], cv[U];
 #pragma unroll
@@ -759,10 +691,7 @@ __device__ __forceinline__ void seq_tile(const Tile tl, int T, float* const* __r
         xv[k][m] = WRITE ? load4_stream<FULL>(x[m] + e[k], n[k]) : load4<FULL>(x[m] + e[k], n[k]);
     f4 ref[U];
 #pragma unroll
-    for (int k = 0; k < U; ++k)
-      ref[k] = (REF == 0)   ? xv[k][0] + mean_offset<M>(xv[k], inv_m)
-               : (REF == 1) ? cv[k]
-                            : load4<FULL>(rf + e[k], n[k]);
+    for (int k = 0; k < U; ++k) ref[k] = (REF == 0) ? xv[k][0] + mean_offset<M>(xv[k], inv_m) : cv[k];
 #pragma unroll
     for (int m = 0; m < M; ++m) {
 #pragma unroll
@@ -783,48 +712,41 @@ __device__ __forceinline__ void seq_tile(const Tile tl, int T, float* const* __r
 template <int M, int U, int REF>
 __global__ __launch_bounds__(kBlock) void k_seq1(const Tile* __restrict__ tiles, const Walk w, int T,
                                                  float* const* __restrict__ xp,
-                                                 const float* const* __restrict__ xcp,
-                                                 const float* const* __restrict__ refp, float pull, float keep,
+                                                 const float* const* __restrict__ xcp, float pull, float keep,
                                                  double* __restrict__ partials, int pstride) {
-  double acc[M];
+  double acc[M + 1];          // column M (the norm of the average) is not formed here: stays zero
   float scale[M];
 #pragma unroll
-  for (int m = 0; m < M; ++m) {
-    acc[m] = 0.0;
-    scale[m] = 0.f;
-  }
+  for (int m = 0; m < M; ++m) scale[m] = 0.f;
+#pragma unroll
+  for (int m = 0; m <= M; ++m) acc[m] = 0.0;
   const float inv_m = 1.0f / static_cast<float>(M);
-  walk_items<false>(
-      w, 1,
-      [&](int t, auto full) {
-        constexpr bool kFull = decltype(full)::value;
-        seq_tile<M, U, REF, false, kFull>(tiles[kFull ? t : w.nfull + t], T, xp, xcp, refp, pull, keep, scale, inv_m,
-                                          acc);
+  walk<false>(
+      w, 1, [&](int t) { seq_tile<M, U, REF, false, true>(tiles[t], T, xp, xcp, pull, keep, scale, inv_m, acc); },
+      [&](int t) {
+        seq_tile<M, U, REF, false, false>(tiles[w.nfull + t], T, xp, xcp, pull, keep, scale, inv_m, acc);
       },
-      [&](int row) { block_sums_flush<M>(acc, partials + static_cast<size_t>(row) * pstride); });
+      [&](int row) { block_sums_flush<M + 1>(acc, partials + static_cast<size_t>(row) * pstride); });
 }
 
 template <int M, int U, int REF>
 __global__ __launch_bounds__(kBlock) void k_seq2(const Tile* __restrict__ tiles, const Walk w, int T,
                                                  float* const* __restrict__ xp,
-                                                 const float* const* __restrict__ xcp,
-                                                 const float* const* __restrict__ refp, float pull, float keep,
+                                                 const float* const* __restrict__ xcp, float pull, float keep,
                                                  float push, const double* __restrict__ partials, int nparts,
                                                  int pstride, float* __restrict__ r_post_out) {
   // lambda / r_m from the partial sums (c = 0 - push/r, so scale = -c; zero distance: no push)
   float c[M], scale[M], inv_r[M];
   bool skip[M];
-  coefficients_from_partials<M>(partials, nparts, pstride, 0.f, push, c, skip, inv_r, r_post_out, nullptr);
+  coefficients_from_partials<M>(partials, nparts, pstride, 0.f, push, c, skip, inv_r, r_post_out, nullptr, nullptr);
 #pragma unroll
   for (int m = 0; m < M; ++m) scale[m] = skip[m] ? 0.f : -c[m];
-  double unused[M];
+  double unused[M + 1];
   const float inv_m = 1.0f / static_cast<float>(M);
-  walk_items<true>(
-      w, 1,
-      [&](int t, auto full) {
-        constexpr bool kFull = decltype(full)::value;
-        seq_tile<M, U, REF, true, kFull>(tiles[kFull ? t : w.nfull + t], T, xp, xcp, refp, pull, keep, scale, inv_m,
-                                         unused);
+  walk<true>(
+      w, 1, [&](int t) { seq_tile<M, U, REF, true, true>(tiles[t], T, xp, xcp, pull, keep, scale, inv_m, unused); },
+      [&](int t) {
+        seq_tile<M, U, REF, true, false>(tiles[w.nfull + t], T, xp, xcp, pull, keep, scale, inv_m, unused);
       },
       [](int) {});
 }
@@ -832,9 +754,6 @@ __global__ __launch_bounds__(kBlock) void k_seq2(const Tile* __restrict__ tiles,
 // ------------------------------------------------------------------ AdamW local step
 // Decoupled weight decay Adam: x <- x (1 - lr wd); m <- b1 m + (1-b1) g; s <- b2 s + (1-b2) g^2;
 // x <- x - lr (m / bc1) / (sqrt(s / bc2) + eps), bc_i = 1 - b_i^t computed on the host.
-struct AdamHyper {
-  float lr, b1, b2, eps, wd, inv_bc1, inv_bc2;
-};
 
 __device__ __forceinline__ void adamw_vec(const f4& xv, const f4& av, const f4& sv, const f4& gv,
                                           const AdamHyper& hp, f4& xn, f4& an, f4& sn) {
@@ -860,8 +779,9 @@ __device__ __forceinline__ void adamw_vec(const f4& xv, const f4& av, const f4& 
 template <int U, bool FULL>
 __device__ __forceinline__ void adamw_tile(float* x, float* m1, float* m2, const float* g, int count,
                                            const AdamHyper hp) {
+  constexpr int kVec = vectors_per_lane(kStepTileElems);
 #pragma unroll 1
-  for (int it = 0; it < kVecPerThread / U; ++it) {
+  for (int it = 0; it < kVec / U; ++it) {
     int e[U], n[U];
     f4 xv[U], av[U], sv[U], gv[U];
 #pragma unroll
@@ -890,25 +810,21 @@ __global__ __launch_bounds__(kBlock) void k_adamw_step(const Tile* __restrict__ 
                                                        float* const* __restrict__ ap, float* const* __restrict__ sp,
                                                        const float* const* __restrict__ gp, const AdamHyper hp) {
   // work items are (pair of full tiles, worker) or (partial tile, worker), worker-major
-  walk_items<false>(
-      w, M,
-      [&](int item, auto full) {
-        constexpr bool kFull = decltype(full)::value;
-        constexpr int kPer = kFull ? kTilesPerWorkerItem : 1;
-        const int ntile = kFull ? w.nfull : w.ntiles - w.nfull;
-        const int per_worker = (ntile + kPer - 1) / kPer;
-        const int m = item / per_worker;
-        const int first = (item - m * per_worker) * kPer;
-        if (m >= M) return;       // cannot happen while the host counts items the same way
+  auto item_tiles = [&](int item, int ntile, int per, int first_tile, auto full) {
+    constexpr bool kFull = decltype(full)::value;
+    const dppf_walk::WorkerItem wi = dppf_walk::worker_item(item, ntile, per);
+    if (wi.worker >= M) return;       // cannot happen while the host counts items the same way
 #pragma unroll 1
-        for (int t = first; t < first + kPer && t < ntile; ++t) {
-          const Tile tl = tiles[(kFull ? 0 : w.nfull) + t];
-          const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
-          adamw_tile<U, kFull>(xp[slot] + tl.offset, ap[slot] + tl.offset, sp[slot] + tl.offset,
-                               gp[slot] + tl.offset, tl.count, hp);
-        }
-      },
-      [](int) {});
+    for (int t = wi.first_tile; t < wi.end_tile; ++t) {
+      const Tile tl = tiles[first_tile + t];
+      const size_t slot = static_cast<size_t>(wi.worker) * T + tl.tensor;
+      adamw_tile<U, kFull>(xp[slot] + tl.offset, ap[slot] + tl.offset, sp[slot] + tl.offset, gp[slot] + tl.offset,
+                           tl.count, hp);
+    }
+  };
+  walk<false>(
+      w, M, [&](int item) { item_tiles(item, w.nfull, kTilesPerWorkerItem, 0, std::true_type{}); },
+      [&](int item) { item_tiles(item, w.ntiles - w.nfull, 1, w.nfull, std::false_type{}); }, [](int) {});
 }
 
 // Sweep 1 of the round with the AdamW step folded in: read x, m1, m2, g of all M workers, step,
@@ -919,12 +835,14 @@ template <int M, int U, bool FULL>
 __device__ __forceinline__ void adamw_reduce_tile(const Tile tl, int T, float* const* __restrict__ xp,
                                                   float* const* __restrict__ ap, float* const* __restrict__ sp,
                                                   const float* const* __restrict__ gp, const AdamHyper hp,
-                                                  float inv_m, double (&acc)[M]) {
-  float part[M];
+                                                  float inv_m, double (&acc)[M + 1]) {
+  constexpr int kVec = vectors_per_lane(sweep_tile_elems(M));
+  static_assert(kVec % U == 0, "a lane's vectors of a tile are taken U at a time");
+  float part[M + 1];
 #pragma unroll
-  for (int m = 0; m < M; ++m) part[m] = 0.f;
+  for (int m = 0; m <= M; ++m) part[m] = 0.f;
 #pragma unroll 1
-  for (int it = 0; it < kVecPerThread / U; ++it) {
+  for (int it = 0; it < kVec / U; ++it) {
     int e[U], n[U];
     f4 xv[U][M];
 #pragma unroll
@@ -955,7 +873,7 @@ __device__ __forceinline__ void adamw_reduce_tile(const Tile tl, int T, float* c
         store4_stream<FULL>(a + e[k], an, n[k]);
         store4_stream<FULL>(q + e[k], sn, n[k]);
         store4<FULL>(x + e[k], xn, n[k]);     // read again by sweep 2
-        xv[k][m] = xn;
+        xv[k][m] = first_components<FULL>(xn, n[k]);
       }
     }
 #pragma unroll
@@ -963,10 +881,11 @@ __device__ __forceinline__ void adamw_reduce_tile(const Tile tl, int T, float* c
       const f4 mo = mean_offset<M>(xv[k], inv_m);
 #pragma unroll
       for (int m = 0; m < M; ++m) part[m] = sumsq4((xv[k][m] - xv[k][0]) - mo, part[m]);
+      part[M] = sumsq4(xv[k][0] + mo, part[M]);
     }
   }
 #pragma unroll
-  for (int m = 0; m < M; ++m) acc[m] += static_cast<double>(part[m]);
+  for (int m = 0; m <= M; ++m) acc[m] += static_cast<double>(part[m]);
 }
 
 template <int M, int U>
@@ -976,26 +895,31 @@ __global__ __launch_bounds__(kBlock) void k_adamw_reduce(const Tile* __restrict_
                                                          float* const* __restrict__ sp,
                                                          const float* const* __restrict__ gp, const AdamHyper hp,
                                                          double* __restrict__ partials, int pstride) {
-  double acc[M];
+  double acc[M + 1];
 #pragma unroll
-  for (int m = 0; m < M; ++m) acc[m] = 0.0;
+  for (int m = 0; m <= M; ++m) acc[m] = 0.0;
   const float inv_m = 1.0f / static_cast<float>(M);
-  walk_items<false>(
-      w, 1,
-      [&](int t, auto full) {
-        constexpr bool kFull = decltype(full)::value;
-        adamw_reduce_tile<M, U, kFull>(tiles[kFull ? t : w.nfull + t], T, xp, ap, sp, gp, hp, inv_m, acc);
-      },
-      [&](int row) { block_sums_flush<M>(acc, partials + static_cast<size_t>(row) * pstride); });
+  walk<false>(
+      w, 1, [&](int t) { adamw_reduce_tile<M, U, true>(tiles[t], T, xp, ap, sp, gp, hp, inv_m, acc); },
+      [&](int t) { adamw_reduce_tile<M, U, false>(tiles[w.nfull + t], T, xp, ap, sp, gp, hp, inv_m, acc); },
+      [&](int row) { block_sums_flush<M + 1>(acc, partials + static_cast<size_t>(row) * pstride); });
 }
 
 // ------------------------------------------------ by-products the paper logs every round
-// out[0] = relaxed MV = (1/M) sum r_m; out[1..M] = pull strength alpha r_m; out[M+1..2M] = lambda.
-__global__ void k_round_stats(const float* __restrict__ r, int M, float pull, float push, float* __restrict__ out) {
+// out[0] = relaxed MV = (1/M) sum r_m; out[1..M] = pull strength alpha r_m; out[M+1..2M] = lambda;
+// with the norm of the average given: out[2M+1] = ||x_A||, out[2M+2] = relaxed MV / ||x_A||.
+__global__ void k_round_stats(const float* __restrict__ r, int M, float pull, float push,
+                              const float* __restrict__ avg_norm, float* __restrict__ out) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     double s = 0.0;
     for (int m = 0; m < M; ++m) s += static_cast<double>(r[m]);
-    out[0] = static_cast<float>(s / M);
+    const double mv = s / M;
+    out[0] = static_cast<float>(mv);
+    if (avg_norm) {
+      const double na = static_cast<double>(avg_norm[0]);
+      out[2 * M + 1] = static_cast<float>(na);
+      out[2 * M + 2] = static_cast<float>(mv / na);
+    }
   }
   for (int m = threadIdx.x; m < M; m += blockDim.x) {
     out[1 + m] = pull * r[m];
@@ -1003,12 +927,17 @@ __global__ void k_round_stats(const float* __restrict__ r, int M, float pull, fl
   }
 }
 
+__global__ void k_copy_scalar(const float* __restrict__ src, float* __restrict__ dst) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) dst[0] = src[0];
+}
+
 // ----------------------------------------------------------------- stand-alone local step
 template <int U, bool FULL>
 __device__ __forceinline__ void local_tile(float* x, float* v, const float* g, int count, float lr,
                                            float mu, float wd) {
+  constexpr int kVec = vectors_per_lane(kStepTileElems);
 #pragma unroll 1
-  for (int it = 0; it < kVecPerThread / U; ++it) {
+  for (int it = 0; it < kVec / U; ++it) {
     int e[U], n[U];
     f4 xv[U], vv[U], gv[U];
 #pragma unroll
@@ -1037,49 +966,50 @@ __global__ __launch_bounds__(kBlock) void k_local_step(const Tile* __restrict__ 
                                                        const float* const* __restrict__ gp, float lr,
                                                        float mu, float wd) {
   // work items are (pair of full tiles, worker) or (partial tile, worker), worker-major
-  walk_items<false>(
-      w, M,
-      [&](int item, auto full) {
-        constexpr bool kFull = decltype(full)::value;
-        constexpr int kPer = kFull ? kTilesPerWorkerItem : 1;
-        const int ntile = kFull ? w.nfull : w.ntiles - w.nfull;
-        const int per_worker = (ntile + kPer - 1) / kPer;
-        const int m = item / per_worker;
-        const int first = (item - m * per_worker) * kPer;
-        if (m >= M) return;       // cannot happen while the host counts items the same way
+  auto item_tiles = [&](int item, int ntile, int per, int first_tile, auto full) {
+    constexpr bool kFull = decltype(full)::value;
+    const dppf_walk::WorkerItem wi = dppf_walk::worker_item(item, ntile, per);
+    if (wi.worker >= M) return;       // cannot happen while the host counts items the same way
 #pragma unroll 1
-        for (int t = first; t < first + kPer && t < ntile; ++t) {
-          const Tile tl = tiles[(kFull ? 0 : w.nfull) + t];
-          const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
-          local_tile<U, kFull>(xp[slot] + tl.offset, vp[slot] + tl.offset, gp[slot] + tl.offset, tl.count, lr, mu, wd);
-        }
-      },
-      [](int) {});
+    for (int t = wi.first_tile; t < wi.end_tile; ++t) {
+      const Tile tl = tiles[first_tile + t];
+      const size_t slot = static_cast<size_t>(wi.worker) * T + tl.tensor;
+      local_tile<U, kFull>(xp[slot] + tl.offset, vp[slot] + tl.offset, gp[slot] + tl.offset, tl.count, lr, mu, wd);
+    }
+  };
+  walk<false>(
+      w, M, [&](int item) { item_tiles(item, w.nfull, kTilesPerWorkerItem, 0, std::true_type{}); },
+      [&](int item) { item_tiles(item, w.ntiles - w.nfull, 1, w.nfull, std::false_type{}); }, [](int) {});
 }
 
-// ------------------------------- average over a runtime number of workers (M > kMaxTemplM)
+// ============================================================ any M: a STORED average is read
+// These kernels walk the tile list of kStepTileElems-element tiles.  A lane holds its four vectors
+// of the average (and of whatever else is per element) and streams the workers past them,
+// kAnyChunk workers' loads in flight at a time.
+constexpr int kAnyVec = vectors_per_lane(kStepTileElems);
+
+// ------------------------------- average over a runtime number of workers
 template <bool FULL>
 __device__ __forceinline__ void mean_any_tile(const Tile tl, int M, int T,
                                               float* const* __restrict__ xp, float* xb, float inv_m) {
-  // Workers are taken kAnyChunk at a time and all of a chunk's loads are issued before the first
-  // is used; the sums still run over the workers in ascending order.
-  f4 x0[kVecPerThread], s[kVecPerThread];
+  // The sums run over the workers in ascending order.
+  f4 x0[kAnyVec], s[kAnyVec];
   const float* base0 = xp[tl.tensor] + tl.offset;
 #pragma unroll
-  for (int it = 0; it < kVecPerThread; ++it) {
+  for (int it = 0; it < kAnyVec; ++it) {
     const int e = 4 * (threadIdx.x + it * kBlock);
     x0[it] = load4<FULL>(base0 + e, FULL ? 4 : tl.count - e);
     s[it] = (f4){0.f, 0.f, 0.f, 0.f};
   }
 #pragma unroll 1
   for (int m = 1; m < M; m += kAnyChunk) {
-    f4 t[kAnyChunk][kVecPerThread];
+    f4 t[kAnyChunk][kAnyVec];
 #pragma unroll
     for (int k = 0; k < kAnyChunk; ++k)
       if (m + k < M) {
         const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
 #pragma unroll
-        for (int it = 0; it < kVecPerThread; ++it) {
+        for (int it = 0; it < kAnyVec; ++it) {
           const int e = 4 * (threadIdx.x + it * kBlock);
           t[k][it] = load4<FULL>(base + e, FULL ? 4 : tl.count - e);
         }
@@ -1088,11 +1018,11 @@ __device__ __forceinline__ void mean_any_tile(const Tile tl, int M, int T,
     for (int k = 0; k < kAnyChunk; ++k)
       if (m + k < M) {
 #pragma unroll
-        for (int it = 0; it < kVecPerThread; ++it) s[it] += t[k][it] - x0[it];
+        for (int it = 0; it < kAnyVec; ++it) s[it] += t[k][it] - x0[it];
       }
   }
 #pragma unroll
-  for (int it = 0; it < kVecPerThread; ++it) {
+  for (int it = 0; it < kAnyVec; ++it) {
     const int e = 4 * (threadIdx.x + it * kBlock);
     store4<FULL>(xb + e, x0[it] + scale_by_inverse_count(s[it], M, inv_m), FULL ? 4 : tl.count - e);
   }
@@ -1102,13 +1032,437 @@ __global__ __launch_bounds__(kBlock) void k_mean_any(const Tile* __restrict__ ti
                                                      float* const* __restrict__ xp,
                                                      float* const* __restrict__ xbarp) {
   const float inv_m = 1.0f / static_cast<float>(M);
-  walk_items<false>(
+  walk<false>(
       w, 1,
-      [&](int t, auto full) {
-        constexpr bool kFull = decltype(full)::value;
-        const Tile tl = tiles[kFull ? t : w.nfull + t];
-        mean_any_tile<kFull>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset, inv_m);
+      [&](int t) {
+        const Tile tl = tiles[t];
+        mean_any_tile<true>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset, inv_m);
       },
+      [&](int t) {
+        const Tile tl = tiles[w.nfull + t];
+        mean_any_tile<false>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset, inv_m);
+      },
+      [](int) {});
+}
+
+// ------------------------------- squared distances to a stored average (columns 0..M-1) and the
+// squared norm of that average (column M)
+template <bool FULL>
+__device__ __forceinline__ void norms_any_tile(const Tile tl, int M, int T, float* const* __restrict__ xp,
+                                               const float* xb, ColumnSums& sums) {
+  f4 xbar[kAnyVec];
+  float pa = 0.f;
+#pragma unroll
+  for (int it = 0; it < kAnyVec; ++it) {
+    const int e = 4 * (threadIdx.x + it * kBlock);
+    xbar[it] = load4<FULL>(xb + e, FULL ? 4 : tl.count - e);
+    pa = sumsq4(xbar[it], pa);
+  }
+  sums.add(pa, M);
+#pragma unroll 1
+  for (int m = 0; m < M; m += kAnyChunk) {
+    f4 t[kAnyChunk][kAnyVec];
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+#pragma unroll
+        for (int it = 0; it < kAnyVec; ++it) {
+          const int e = 4 * (threadIdx.x + it * kBlock);
+          t[k][it] = load4_stream<FULL>(base + e, FULL ? 4 : tl.count - e);
+        }
+      }
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+        float p = 0.f;
+#pragma unroll
+        for (int it = 0; it < kAnyVec; ++it) p = sumsq4(t[k][it] - xbar[it], p);   // past a partial tile's end: 0 - 0
+        sums.add(p, m + k);
+      }
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_norms_any(const Tile* __restrict__ tiles, const Walk w, int M, int T,
+                                                      float* const* __restrict__ xp,
+                                                      const float* const* __restrict__ xbarp,
+                                                      double* __restrict__ partials, int pstride) {
+  extern __shared__ double lds_cols[];
+  ColumnSums sums;
+  sums.init(lds_cols, M + 1);
+  walk<false>(
+      w, 1,
+      [&](int t) {
+        const Tile tl = tiles[t];
+        norms_any_tile<true>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset, sums);
+      },
+      [&](int t) {
+        const Tile tl = tiles[w.nfull + t];
+        norms_any_tile<false>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset, sums);
+      },
+      [&](int row) { sums.flush(partials + static_cast<size_t>(row) * pstride); });
+}
+
+// ------------------------------- Eq. 5 (EXACT = false) or Eq. 4 (a) (EXACT = true) with the average
+// (and, for the exact form, the sum of unit gap vectors S = sum_j (x_A - x_j)/r_j) read from memory:
+//   x_m + (x_A - x_m) c_m [+ k2 S]
+template <bool EXACT, bool FULL>
+__device__ __forceinline__ void update_any_tile(const Tile tl, int M, int T, float* const* __restrict__ xp,
+                                                const float* xb, const float* us, const Coef* __restrict__ coef,
+                                                float k2) {
+  f4 xbar[kAnyVec], usum[kAnyVec];
+#pragma unroll
+  for (int it = 0; it < kAnyVec; ++it) {
+    const int e = 4 * (threadIdx.x + it * kBlock);
+    xbar[it] = load4_stream<FULL>(xb + e, FULL ? 4 : tl.count - e);
+    if (EXACT) usum[it] = load4_stream<FULL>(us + e, FULL ? 4 : tl.count - e);
+  }
+#pragma unroll 1
+  for (int m = 0; m < M; m += kAnyChunk) {
+    f4 t[kAnyChunk][kAnyVec];
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+#pragma unroll
+        for (int it = 0; it < kAnyVec; ++it) {
+          const int e = 4 * (threadIdx.x + it * kBlock);
+          t[k][it] = load4_stream<FULL>(base + e, FULL ? 4 : tl.count - e);
+        }
+      }
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+        float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+        const float c = coef[m + k].c;
+        const bool stay = !EXACT && coef[m + k].skip != 0;
+#pragma unroll
+        for (int it = 0; it < kAnyVec; ++it) {
+          const int e = 4 * (threadIdx.x + it * kBlock);
+          f4 moved = fma4(xbar[it] - t[k][it], c, t[k][it]);
+          if (EXACT) moved = fma4(usum[it], k2, moved);
+          store4_stream<FULL>(base + e, stay ? t[k][it] : moved, FULL ? 4 : tl.count - e);
+        }
+      }
+  }
+}
+
+template <bool EXACT>
+__global__ __launch_bounds__(kBlock) void k_update_any(const Tile* __restrict__ tiles, const Walk w, int M, int T,
+                                                       float* const* __restrict__ xp,
+                                                       const float* const* __restrict__ xbarp,
+                                                       const float* const* __restrict__ sump,
+                                                       const Coef* __restrict__ coef, float k2) {
+  walk<false>(
+      w, 1,
+      [&](int t) {
+        const Tile tl = tiles[t];
+        update_any_tile<EXACT, true>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset,
+                                     EXACT ? sump[tl.tensor] + tl.offset : nullptr, coef, k2);
+      },
+      [&](int t) {
+        const Tile tl = tiles[w.nfull + t];
+        update_any_tile<EXACT, false>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset,
+                                      EXACT ? sump[tl.tensor] + tl.offset : nullptr, coef, k2);
+      },
+      [](int) {});
+}
+
+// ------------------------------- S = sum_j (x_A - x_j) / r_j of the exact update, stored
+template <bool FULL>
+__device__ __forceinline__ void unit_sum_tile(const Tile tl, int M, int T, float* const* __restrict__ xp,
+                                              const float* xb, const Coef* __restrict__ coef, float* out) {
+  // the sum runs over the workers in ascending order
+  f4 xbar[kAnyVec], s[kAnyVec];
+#pragma unroll
+  for (int it = 0; it < kAnyVec; ++it) {
+    const int e = 4 * (threadIdx.x + it * kBlock);
+    xbar[it] = load4<FULL>(xb + e, FULL ? 4 : tl.count - e);
+    s[it] = (f4){0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll 1
+  for (int m = 0; m < M; m += kAnyChunk) {
+    f4 t[kAnyChunk][kAnyVec];
+    float wgt[kAnyChunk];
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+        wgt[k] = coef[m + k].inv_r;
+#pragma unroll
+        for (int it = 0; it < kAnyVec; ++it) {
+          const int e = 4 * (threadIdx.x + it * kBlock);
+          t[k][it] = load4<FULL>(base + e, FULL ? 4 : tl.count - e);
+        }
+      }
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+#pragma unroll
+        for (int it = 0; it < kAnyVec; ++it) s[it] = fma4(xbar[it] - t[k][it], wgt[k], s[it]);
+      }
+  }
+#pragma unroll
+  for (int it = 0; it < kAnyVec; ++it) {
+    const int e = 4 * (threadIdx.x + it * kBlock);
+    store4<FULL>(out + e, s[it], FULL ? 4 : tl.count - e);
+  }
+}
+
+__global__ __launch_bounds__(kBlock) void k_unit_sum_any(const Tile* __restrict__ tiles, const Walk w, int M, int T,
+                                                         float* const* __restrict__ xp,
+                                                         const float* const* __restrict__ xbarp,
+                                                         const Coef* __restrict__ coef,
+                                                         float* const* __restrict__ sump) {
+  walk<false>(
+      w, 1,
+      [&](int t) {
+        const Tile tl = tiles[t];
+        unit_sum_tile<true>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset, coef, sump[tl.tensor] + tl.offset);
+      },
+      [&](int t) {
+        const Tile tl = tiles[w.nfull + t];
+        unit_sum_tile<false>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset, coef, sump[tl.tensor] + tl.offset);
+      },
+      [](int) {});
+}
+
+// ------------------------------- Alg. 1 literally for any M: the reference point of the push is x_C
+// (REF = 1) or a stored average (REF = 2).  WRITE = false accumulates the squared norms of the
+// pulled gaps, WRITE = true applies pull and push with lambda / r_m = -coef[m].c.
+template <int REF, bool WRITE, bool FULL>
+__device__ __forceinline__ void seq_any_tile(const Tile tl, int M, int T, float* const* __restrict__ xp,
+                                             const float* xc, const float* rf, float pull, float keep,
+                                             const Coef* __restrict__ coef, ColumnSums& sums) {
+  f4 cv[kAnyVec], ref[kAnyVec];
+#pragma unroll
+  for (int it = 0; it < kAnyVec; ++it) {
+    const int e = 4 * (threadIdx.x + it * kBlock);
+    cv[it] = load4<FULL>(xc + e, FULL ? 4 : tl.count - e);
+    ref[it] = (REF == 1) ? cv[it] : load4<FULL>(rf + e, FULL ? 4 : tl.count - e);
+  }
+#pragma unroll 1
+  for (int m = 0; m < M; m += kAnyChunk) {
+    f4 t[kAnyChunk][kAnyVec];
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+#pragma unroll
+        for (int it = 0; it < kAnyVec; ++it) {
+          const int e = 4 * (threadIdx.x + it * kBlock);
+          t[k][it] = WRITE ? load4_stream<FULL>(base + e, FULL ? 4 : tl.count - e)
+                           : load4<FULL>(base + e, FULL ? 4 : tl.count - e);
+        }
+      }
+#pragma unroll
+    for (int k = 0; k < kAnyChunk; ++k)
+      if (m + k < M) {
+        float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+        const float scale = WRITE ? (coef[m + k].skip != 0 ? 0.f : -coef[m + k].c) : 0.f;
+        float p = 0.f;
+#pragma unroll
+        for (int it = 0; it < kAnyVec; ++it) {
+          const int e = 4 * (threadIdx.x + it * kBlock);
+          const f4 pulled = fma4(cv[it], pull, t[k][it] * keep);
+          const f4 gap = pulled - ref[it];
+          if (WRITE) store4_stream<FULL>(base + e, fma4(gap, scale, pulled), FULL ? 4 : tl.count - e);
+          else p = sumsq4(gap, p);       // lanes past a partial tile's end hold zeros throughout
+        }
+        if (!WRITE) sums.add(p, m + k);
+      }
+  }
+}
+
+template <int REF, bool WRITE>
+__global__ __launch_bounds__(kBlock) void k_seq_any(const Tile* __restrict__ tiles, const Walk w, int M, int T,
+                                                    float* const* __restrict__ xp,
+                                                    const float* const* __restrict__ xcp,
+                                                    const float* const* __restrict__ refp, float pull, float keep,
+                                                    const Coef* __restrict__ coef, double* __restrict__ partials,
+                                                    int pstride) {
+  extern __shared__ double lds_cols[];
+  ColumnSums sums;
+  if (!WRITE) sums.init(lds_cols, M + 1);
+  walk<false>(
+      w, 1,
+      [&](int t) {
+        const Tile tl = tiles[t];
+        seq_any_tile<REF, WRITE, true>(tl, M, T, xp, xcp[tl.tensor] + tl.offset,
+                                       REF == 2 ? refp[tl.tensor] + tl.offset : nullptr, pull, keep, coef, sums);
+      },
+      [&](int t) {
+        const Tile tl = tiles[w.nfull + t];
+        seq_any_tile<REF, WRITE, false>(tl, M, T, xp, xcp[tl.tensor] + tl.offset,
+                                        REF == 2 ? refp[tl.tensor] + tl.offset : nullptr, pull, keep, coef, sums);
+      },
+      [&](int row) {
+        if (!WRITE) sums.flush(partials + static_cast<size_t>(row) * pstride);
+      });
+}
+
+// ======================================================= 17 <= M <= 39: staged in LDS
+// A tile is kLdsTileElems elements: one 16-byte vector per lane.  A lane streams the workers
+// through registers kLdsChunk at a time (the next chunk's loads are issued before the current
+// chunk is processed), parks every worker's vector in its own LDS column, and once the average is
+// known reads them back.  LDS holds M x 256 vectors (4 KB per worker) and, for the reducing
+// sweep, the per-wave running sums.
+
+template <int OPT, bool FULL>
+struct LdsChunk {
+  f4 x[kLdsChunk], a[kLdsChunk], s[kLdsChunk], g[kLdsChunk];
+  __device__ __forceinline__ void load(int m0, int M, int T, const Tile& tl, int e, int n, float* const* xp,
+                                       const LdsOptArgs& o) {
+#pragma unroll
+    for (int k = 0; k < kLdsChunk; ++k)
+      if (m0 + k < M) {
+        const size_t slot = static_cast<size_t>(m0 + k) * T + tl.tensor;
+        x[k] = load4_stream<FULL>(xp[slot] + tl.offset + e, n);
+        if (OPT != 0) {
+          a[k] = load4_stream<FULL>(o.vp[slot] + tl.offset + e, n);
+          g[k] = load4_stream<FULL>(o.gp[slot] + tl.offset + e, n);
+        }
+        if (OPT == 2) s[k] = load4_stream<FULL>(o.sp[slot] + tl.offset + e, n);
+      }
+  }
+  // the k-th worker's x after the folded step (its state is stored on the way)
+  __device__ __forceinline__ f4 stepped(int k, int m, int T, const Tile& tl, int e, int n, float* const* xp,
+                                        const LdsOptArgs& o) {
+    if (OPT == 0) return x[k];
+    const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
+    if (OPT == 1) {
+      const f4 ge = fma4(x[k], o.wd, g[k]);
+      const f4 vn = fma4(a[k], o.mu, ge);
+      store4_stream<FULL>(o.vp[slot] + tl.offset + e, vn, n);
+      return fma4(vn, -o.lr, x[k]);
+    }
+    f4 xn, an, sn;
+    adamw_vec(x[k], a[k], s[k], g[k], o.adam, xn, an, sn);
+    store4_stream<FULL>(o.vp[slot] + tl.offset + e, an, n);
+    store4_stream<FULL>(o.sp[slot] + tl.offset + e, sn, n);
+    store4<FULL>(xp[slot] + tl.offset + e, xn, n);     // read again by sweep 2
+    return first_components<FULL>(xn, n);
+  }
+};
+
+template <int OPT, int XBAR, bool FULL>
+__device__ __forceinline__ void sweep1_lds_tile(const Tile tl, int M, int T, float* const* __restrict__ xp,
+                                                const LdsOptArgs& o, float* const* __restrict__ xbarp, float inv_m,
+                                                f4* stage, ColumnSums& sums) {
+  const int e = 4 * threadIdx.x;
+  const int n = FULL ? 4 : tl.count - e;
+  f4 x0 = {0.f, 0.f, 0.f, 0.f}, s = {0.f, 0.f, 0.f, 0.f};
+  LdsChunk<OPT, FULL> ca, cb;
+  auto consume = [&](LdsChunk<OPT, FULL>& c, int m0) {
+#pragma unroll
+    for (int k = 0; k < kLdsChunk; ++k)
+      if (m0 + k < M) {
+        const f4 xn = c.stepped(k, m0 + k, T, tl, e, n, xp, o);
+        stage[(m0 + k) * kBlock + threadIdx.x] = xn;
+        if (m0 + k == 0) x0 = xn;
+        else s += xn - x0;
+      }
+  };
+  ca.load(0, M, T, tl, e, n, xp, o);
+#pragma unroll 1
+  for (int m0 = 0; m0 < M; m0 += 2 * kLdsChunk) {
+    cb.load(m0 + kLdsChunk, M, T, tl, e, n, xp, o);
+    consume(ca, m0);
+    ca.load(m0 + 2 * kLdsChunk, M, T, tl, e, n, xp, o);
+    consume(cb, m0 + kLdsChunk);
+  }
+  const f4 mo = scale_by_inverse_count(s, M, inv_m);
+  const f4 xa = x0 + mo;
+  if (XBAR == 1) store4_stream<FULL>(xbarp[tl.tensor] + tl.offset + e, xa, n);
+  sums.add(sumsq4(xa, 0.f), M);
+#pragma unroll 4
+  for (int m = 0; m < M; ++m) {
+    const f4 xm = stage[m * kBlock + threadIdx.x];     // this lane's own column: no barrier needed
+    sums.add(sumsq4((xm - x0) - mo, 0.f), m);
+  }
+}
+
+template <int OPT, int XBAR>
+__global__ __launch_bounds__(kBlock) void k_sweep1_lds(const Tile* __restrict__ tiles, const Walk w, int M, int T,
+                                                       float* const* __restrict__ xp, const LdsOptArgs o,
+                                                       float* const* __restrict__ xbarp,
+                                                       double* __restrict__ partials, int pstride) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  f4* stage = reinterpret_cast<f4*>(lds_raw);
+  ColumnSums sums;
+  sums.init(reinterpret_cast<double*>(lds_raw + static_cast<size_t>(M) * kBlock * sizeof(f4)), M + 1);
+  const float inv_m = 1.0f / static_cast<float>(M);
+  walk<false>(
+      w, 1, [&](int t) { sweep1_lds_tile<OPT, XBAR, true>(tiles[t], M, T, xp, o, xbarp, inv_m, stage, sums); },
+      [&](int t) { sweep1_lds_tile<OPT, XBAR, false>(tiles[w.nfull + t], M, T, xp, o, xbarp, inv_m, stage, sums); },
+      [&](int row) { sums.flush(partials + static_cast<size_t>(row) * pstride); });
+}
+
+// MODE: 0 = Eq. 5; 1 = Eq. 5 on x - lr v (fused momentum-SGD round: x in memory is still the old
+// value, v already the new momentum); 2 = the exact two-term update of Eq. 4 (a).
+template <int MODE, bool FULL>
+__device__ __forceinline__ void sweep2_lds_tile(const Tile tl, int M, int T, float* const* __restrict__ xp,
+                                                const float* const* __restrict__ vp, float lr,
+                                                const Coef* __restrict__ coef, float k2, float inv_m, f4* stage) {
+  const int e = 4 * threadIdx.x;
+  const int n = FULL ? 4 : tl.count - e;
+  f4 x0 = {0.f, 0.f, 0.f, 0.f}, s = {0.f, 0.f, 0.f, 0.f};
+  f4 ax[kLdsChunk], av[kLdsChunk], bx[kLdsChunk], bv[kLdsChunk];
+  auto load = [&](f4 (&cx)[kLdsChunk], f4 (&cv)[kLdsChunk], int m0) {
+#pragma unroll
+    for (int k = 0; k < kLdsChunk; ++k)
+      if (m0 + k < M) {
+        const size_t slot = static_cast<size_t>(m0 + k) * T + tl.tensor;
+        cx[k] = load4_stream<FULL>(xp[slot] + tl.offset + e, n);
+        if (MODE == 1) cv[k] = load4_stream<FULL>(vp[slot] + tl.offset + e, n);
+      }
+  };
+  auto consume = [&](f4 (&cx)[kLdsChunk], f4 (&cv)[kLdsChunk], int m0) {
+#pragma unroll
+    for (int k = 0; k < kLdsChunk; ++k)
+      if (m0 + k < M) {
+        const f4 xn = (MODE == 1) ? fma4(cv[k], -lr, cx[k]) : cx[k];
+        stage[(m0 + k) * kBlock + threadIdx.x] = xn;
+        if (m0 + k == 0) x0 = xn;
+        else s += xn - x0;
+      }
+  };
+  load(ax, av, 0);
+#pragma unroll 1
+  for (int m0 = 0; m0 < M; m0 += 2 * kLdsChunk) {
+    load(bx, bv, m0 + kLdsChunk);
+    consume(ax, av, m0);
+    load(ax, av, m0 + 2 * kLdsChunk);
+    consume(bx, bv, m0 + kLdsChunk);
+  }
+  const f4 mo = scale_by_inverse_count(s, M, inv_m);
+  f4 usum = {0.f, 0.f, 0.f, 0.f};
+  if (MODE == 2) {
+#pragma unroll 4
+    for (int m = 0; m < M; ++m)
+      usum = fma4(mo - (stage[m * kBlock + threadIdx.x] - x0), coef[m].inv_r, usum);
+  }
+#pragma unroll 4
+  for (int m = 0; m < M; ++m) {
+    const f4 xm = stage[m * kBlock + threadIdx.x];
+    f4 moved = fma4(mo - (xm - x0), coef[m].c, xm);
+    if (MODE == 2) moved = fma4(usum, k2, moved);
+    const bool stay = MODE != 2 && coef[m].skip != 0;
+    store4_stream<FULL>(xp[static_cast<size_t>(m) * T + tl.tensor] + tl.offset + e, stay ? xm : moved, n);
+  }
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kBlock) void k_sweep2_lds(const Tile* __restrict__ tiles, const Walk w, int M, int T,
+                                                       float* const* __restrict__ xp,
+                                                       const float* const* __restrict__ vp, float lr,
+                                                       const Coef* __restrict__ coef, float k2) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  f4* stage = reinterpret_cast<f4*>(lds_raw);
+  const float inv_m = 1.0f / static_cast<float>(M);
+  walk<true>(
+      w, 1, [&](int t) { sweep2_lds_tile<MODE, true>(tiles[t], M, T, xp, vp, lr, coef, k2, inv_m, stage); },
+      [&](int t) { sweep2_lds_tile<MODE, false>(tiles[w.nfull + t], M, T, xp, vp, lr, coef, k2, inv_m, stage); },
       [](int) {});
 }
 
@@ -1117,18 +1471,18 @@ __global__ __launch_bounds__(kBlock) void k_mean_any(const Tile* __restrict__ ti
 // (full tiles first, then the ragged tail, exactly what the host-side list builder produces) and
 // the table of the M workers' base pointers x + m*ld are written straight into caller-provided
 // device memory, and the on-demand counter is put back to zero.
-__global__ __launch_bounds__(kBlock) void k_flat_setup(Tile* __restrict__ tiles, long long d,
+__global__ __launch_bounds__(kBlock) void k_flat_setup(Tile* __restrict__ tiles, long long d, int tile_elems,
                                                        float** __restrict__ ptrs, float* x, long long ld, int M,
                                                        Sched* __restrict__ sched) {
-  const long long nfull = d / kTileElems;
-  const int tail = static_cast<int>(d - nfull * kTileElems);
+  const long long nfull = d / tile_elems;
+  const int tail = static_cast<int>(d - nfull * tile_elems);
   const long long ntiles = nfull + (tail > 0 ? 1 : 0);
   const long long stride = static_cast<long long>(gridDim.x) * kBlock;
   for (long long t = static_cast<long long>(blockIdx.x) * kBlock + threadIdx.x; t < ntiles; t += stride) {
     Tile tl;
-    tl.offset = t * kTileElems;
+    tl.offset = t * tile_elems;
     tl.tensor = 0;
-    tl.count = t < nfull ? kTileElems : tail;
+    tl.count = t < nfull ? tile_elems : tail;
     tiles[t] = tl;
   }
   if (blockIdx.x == 0) {
@@ -1138,72 +1492,6 @@ __global__ __launch_bounds__(kBlock) void k_flat_setup(Tile* __restrict__ tiles,
       sched->done = 0u;
     }
   }
-}
-
-// ---------------------------------------------- plain copy (bandwidth / counter calibration)
-__global__ __launch_bounds__(kBlock) void k_copy(float* __restrict__ dst, const float* __restrict__ src,
-                                                 long long n) {
-  const long long nvec = n / 4;
-  const long long stride = static_cast<long long>(gridDim.x) * kBlock;
-  for (long long i = static_cast<long long>(blockIdx.x) * kBlock + threadIdx.x; i < nvec; i += stride)
-    store4_stream<true>(dst + 4 * i, load4_stream<true>(src + 4 * i, 4), 4);
-  if (blockIdx.x == 0 && threadIdx.x < n - 4 * nvec) dst[4 * nvec + threadIdx.x] = src[4 * nvec + threadIdx.x];
-}
-
-// ------------------------------------ streaming probe: R read streams, W write streams
-// Stream k is the n floats at base + k*stride.  Each element's R values are added and the sum
-// (times w+1) is stored to W streams: streams R..R+W-1, or, with INPLACE, streams 0..W-1 (read
-// and written by the same lane).  Gives the device's practical bandwidth for a given read/write
-// mix, the ceiling the DPPF kernels are compared with.  The blocks walk items of kProbeItemTiles
-// tiles the way the DPPF kernels walk their tiles (walk_items): an even split, or an even split
-// with the tail handed out on demand.
-constexpr int kProbeItemTiles = 16;
-__device__ Sched g_probe_sched;
-
-template <int R, int W, int U, bool INPLACE>
-__global__ __launch_bounds__(kBlock) void k_probe(float* __restrict__ base, long long stride, long long n,
-                                                  float* __restrict__ sink, const Walk walk) {
-  const long long tile = static_cast<long long>(kBlock) * U * 4;
-  const long long ntiles = n / tile;
-  f4 acc = {0.f, 0.f, 0.f, 0.f};
-  walk_items<false>(
-      walk, 1,
-      [&](int item, auto) {
-        const long long t0 = static_cast<long long>(item) * kProbeItemTiles;
-        const long long t1 = t0 + kProbeItemTiles < ntiles ? t0 + kProbeItemTiles : ntiles;
-#pragma unroll 1
-        for (long long t = t0; t < t1; ++t) {
-          f4 v[U];
-#pragma unroll
-          for (int k = 0; k < U; ++k)
-            v[k] = (R > 0) ? (f4){0.f, 0.f, 0.f, 0.f} : (f4){1.f, 2.f, 3.f, static_cast<float>(t)};
-          if (R > 0) {
-            f4 tmp[R > 0 ? R : 1][U];
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-              for (int k = 0; k < U; ++k)
-                tmp[r][k] = load4_stream<true>(base + r * stride + t * tile + 4 * (k * kBlock + threadIdx.x), 4);
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-              for (int k = 0; k < U; ++k) v[k] += tmp[r][k];
-          }
-          if (W > 0) {
-#pragma unroll
-            for (int w = 0; w < W; ++w)
-#pragma unroll
-              for (int k = 0; k < U; ++k)
-                store4_stream<true>(base + (INPLACE ? w : R + w) * stride + t * tile + 4 * (k * kBlock + threadIdx.x),
-                                    v[k] * static_cast<float>(w + 1), 4);
-          } else {
-#pragma unroll
-            for (int k = 0; k < U; ++k) acc += v[k];
-          }
-        }
-      },
-      [](int) {});
-  if (W == 0 && acc.x + acc.y + acc.z + acc.w == 123.456f) sink[0] = acc.x;   // keeps the loads alive
 }
 
 }  // namespace

@@ -1,4 +1,4 @@
-"""ctypes binding of the DPPF C-ABI library (include/dppf.h).
+"""ctypes binding of the DPPF C-ABI library (include/dppf.h, include/dppf_util.h).
 
 Argument marshalling only: every step of the round runs in the library's HIP kernels.
 PyTorch supplies device memory (``tensor.data_ptr()``) and the stream; nothing here computes.
@@ -43,9 +43,11 @@ def load():
         "dppf_plan_create": (ctypes.c_int, [ctypes.POINTER(vp), ctypes.c_int, ctypes.c_int, ctypes.POINTER(i64)]),
         "dppf_plan_destroy": (ctypes.c_int, [vp]),
         "dppf_plan_dim": (i64, [vp]),
-        "dppf_layout_tiles": (ctypes.c_int, [ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64),
-                                             ctypes.POINTER(i64), i64, ctypes.POINTER(ctypes.c_int32),
-                                             ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_int32)]),
+        "dppf_sweep_tile_elems": (ctypes.c_int, [ctypes.c_int]),
+        "dppf_layout_tiles": (ctypes.c_int, [ctypes.c_int, ctypes.c_int, ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                             ctypes.POINTER(i64), ctypes.POINTER(i64), i64,
+                                             ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(i64),
+                                             ctypes.POINTER(ctypes.c_int32)]),
         "dppf_replica_mean": (ctypes.c_int, [vp, c_fpp, c_fpp, vp]),
         "dppf_dist_norms": (ctypes.c_int, [vp, c_fpp, c_fpp, vp, vp]),
         "dppf_pull_push_round": (ctypes.c_int, [vp, c_fpp, f, f, vp, vp, c_fpp, vp]),
@@ -59,7 +61,8 @@ def load():
         "dppf_pull_then_push": (ctypes.c_int, [vp, c_fpp, c_fpp, f, f, ctypes.c_int, vp, vp]),
         "dppf_local_adamw_step": (ctypes.c_int, [vp, c_fpp, c_fpp, c_fpp, c_fpp, f, f, f, f, f, i64, vp]),
         "dppf_round_adamw": (ctypes.c_int, [vp, c_fpp, c_fpp, c_fpp, c_fpp, f, f, f, f, f, i64, f, f, vp, vp, vp]),
-        "dppf_round_statistics": (ctypes.c_int, [vp, ctypes.c_int, f, f, vp, vp]),
+        "dppf_plan_average_norm": (ctypes.c_int, [vp, vp, vp]),
+        "dppf_round_statistics": (ctypes.c_int, [vp, ctypes.c_int, f, f, vp, vp, vp]),
         "dppf_push_schedule": (f, [ctypes.c_int, f, i64, i64]),
         "dppf_util_copy": (ctypes.c_int, [vp, vp, i64, vp]),
         "dppf_util_stream_probe": (ctypes.c_int, [vp, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
@@ -245,6 +248,10 @@ class Plan:
                                          pull, push, _dev(r_out), _dev(c_out), _dev(xbar_out),
                                          _stream(stream)), "dppf_round_flat")
 
+    def average_norm(self, out, stream=None) -> None:
+        """out[0] (device) = ||x_A|| of the most recent round enqueued on this plan."""
+        _check(self._lib.dppf_plan_average_norm(self._h, _dev(out), _stream(stream)), "dppf_plan_average_norm")
+
     # ---- per-kernel timing
     def timing_enable(self, enable: bool = True) -> None:
         _check(self._lib.dppf_plan_timing_enable(self._h, 1 if enable else 0), "dppf_plan_timing_enable")
@@ -269,9 +276,10 @@ def util_copy(dst, src, n: int, stream=None) -> None:
     _check(load().dppf_util_copy(_dev(dst), _dev(src), n, _stream(stream)), "dppf_util_copy")
 
 
-def round_statistics(r, M: int, pull: float, push: float, out, stream=None) -> None:
-    """out[0] = mean distance, out[1..M] = pull strengths, out[M+1..2M] = push strength (device)."""
-    _check(load().dppf_round_statistics(_dev(r), M, pull, push, _dev(out), _stream(stream)),
+def round_statistics(r, M: int, pull: float, push: float, out, avg_norm=None, stream=None) -> None:
+    """out[0] = mean distance, out[1..M] = pull strengths, out[M+1..2M] = push strength; with avg_norm
+    (device, 1 float) also out[2M+1] = ||x_A|| and out[2M+2] = mean distance / ||x_A||.  out: device, 2M+3."""
+    _check(load().dppf_round_statistics(_dev(r), M, pull, push, _dev(avg_norm), _dev(out), _stream(stream)),
            "dppf_round_statistics")
 
 
@@ -289,16 +297,27 @@ def util_stream_probe(base, stride: int, n: int, reads: int, writes: int, inplac
                                          1 if on_demand else 0, _stream(stream)), "dppf_util_stream_probe")
 
 
-def layout_tiles(numel: Sequence[int]):
-    """(d, nfull, tiles) for a tensor list; tiles = list of (tensor, offset, count).  Host only."""
+def sweep_tile_elems(M: int) -> int:
+    """Elements per tile of the round's sweeps for M workers.  Host only."""
+    n = load().dppf_sweep_tile_elems(M)
+    _check(n, "dppf_sweep_tile_elems")
+    return n
+
+
+STEP_TILE_ELEMS = 4096
+
+
+def layout_tiles(numel: Sequence[int], tile_elems: int = STEP_TILE_ELEMS):
+    """(d, nfull, tiles) for a tensor list cut into tiles of tile_elems elements; tiles = list of
+    (tensor, offset, count).  Host only."""
     lib = load()
     T = len(numel)
     arr = (ctypes.c_int64 * max(T, 1))(*[int(n) for n in numel])
     d, nfull, ntiles = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
-    _check(lib.dppf_layout_tiles(T, arr, ctypes.byref(d), ctypes.byref(nfull), ctypes.byref(ntiles), 0, None, None,
-                                 None), "dppf_layout_tiles")
+    _check(lib.dppf_layout_tiles(tile_elems, T, arr, ctypes.byref(d), ctypes.byref(nfull), ctypes.byref(ntiles), 0,
+                                 None, None, None), "dppf_layout_tiles")
     n = ntiles.value
     tt, to, tc = (ctypes.c_int32 * max(n, 1))(), (ctypes.c_int64 * max(n, 1))(), (ctypes.c_int32 * max(n, 1))()
-    _check(lib.dppf_layout_tiles(T, arr, ctypes.byref(d), ctypes.byref(nfull), ctypes.byref(ntiles), n, tt, to, tc),
-           "dppf_layout_tiles")
+    _check(lib.dppf_layout_tiles(tile_elems, T, arr, ctypes.byref(d), ctypes.byref(nfull), ctypes.byref(ntiles), n, tt,
+                                 to, tc), "dppf_layout_tiles")
     return d.value, nfull.value, [(tt[i], to[i], tc[i]) for i in range(n)]

@@ -40,7 +40,8 @@ class DppfLoop:
         dev = x[0][0].device
         self.r = torch.zeros(self.M, device=dev)          # distances measured by the latest round
         self.c = torch.zeros(self.M, device=dev)          # coefficients alpha - lambda/r of that round
-        self.stats = torch.zeros(2 * self.M + 1, device=dev)
+        self.stats = torch.zeros(2 * self.M + 3, device=dev)
+        self.avg_norm = torch.zeros(1, device=dev)
         self.push_used = self.push
         self._params = None                                # set by from_modules
 
@@ -92,11 +93,12 @@ class DppfLoop:
         return True
 
     def round_statistics(self):
-        """(relaxed MV, pull strengths alpha*r_m, push strength) of the latest round, as the
-        appendix's ablation logs them.  Synchronises."""
-        dppf.round_statistics(self.r, self.M, self.pull, self.push_used, self.stats)
+        """(relaxed MV, pull strengths alpha*r_m, push strength, ||x_A||) of the latest round, as the
+        appendix's ablations log them.  Synchronises."""
+        self.plan.average_norm(self.avg_norm)
+        dppf.round_statistics(self.r, self.M, self.pull, self.push_used, self.stats, avg_norm=self.avg_norm)
         out = self.stats.cpu().numpy()
-        return float(out[0]), out[1:self.M + 1].copy(), float(out[self.M + 1])
+        return float(out[0]), out[1:self.M + 1].copy(), float(out[self.M + 1]), float(out[2 * self.M + 1])
 
     def average(self, out: List) -> None:
         """x_A, the value Alg. 1 returns, into the T tensors of `out`."""

@@ -135,3 +135,12 @@ def assert_update_close(gpu_new: np.ndarray, ref_new: np.ndarray, x_pre: np.ndar
             continue
         diff = np.linalg.norm((gpu_new[m].astype(np.float64) - x_pre[m]) - upd)
         assert diff <= 1e-3 * nrm, f"{what}: worker {m} update error {diff / nrm:.3e}"
+
+
+def assert_average_norm(plan, x_avg: np.ndarray, what: str):
+    """The norm of the average the most recent round on `plan` formed, against the oracle's."""
+    import torch
+    out = torch.full((1,), -1.0, device="cuda")
+    plan.average_norm(out)
+    want = O.round_statistics(np.ones(1), 0.0, 0.0, x_avg=x_avg)["average_norm"]
+    assert_rel(out.cpu().numpy()[0], want, 1e-4, what + ": norm of the average")

@@ -19,10 +19,13 @@ def lib():
 
 
 def header_symbols():
-    with open(os.path.join(ROOT, "include", "dppf.h")) as f:
-        text = f.read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(dppf_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in ("dppf.h", "dppf_util.h"):
+        with open(os.path.join(ROOT, "include", header)) as f:
+            text = f.read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(dppf_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -83,7 +86,8 @@ def test_push_schedule_is_a_host_function(lib):
     assert abs(lib.dppf_push_schedule(1, 0.5, 5, 10) - 0.25) < 1e-7
     assert abs(lib.dppf_push_schedule(2, 0.5, 10, 10) - 0.5) < 1e-7
     assert abs(lib.dppf_push_schedule(2, 0.5, 25, 100) - 0.25 * (1 - math.sqrt(0.5))) < 1e-7
-    assert lib.dppf_round_statistics(None, 4, 0.1, 0.1, None, None) == -1
+    assert lib.dppf_round_statistics(None, 4, 0.1, 0.1, None, None, None) == -1
+    assert lib.dppf_plan_average_norm(None, None, None) == -1
     assert lib.dppf_pull_then_push(None, None, None, 0.1, 0.1, 0, None, None) == -1
     assert lib.dppf_pull_push_round_exact(None, None, 0.1, 0.1, None, None, None) == -1
     assert lib.dppf_local_adamw_step(None, None, None, None, None, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, None) == -1
@@ -101,28 +105,34 @@ def test_tile_layout_covers_every_element_exactly_once(lib):
     from paper_2507_20424_amd import dppf, workloads as W
     lists = [[], [0], [1], [4095], [4096], [4097], [3, 0, 8192, 1, 12289, 0, 5], list(W.SPECS["pyramidnet_M8"].numel),
              list(W.SPECS["vitb16_M4"].numel)]
-    for numel in lists:
-        d, nfull, tiles = dppf.layout_tiles(numel)
-        assert d == sum(numel)
-        assert nfull == sum(n // 4096 for n in numel)
-        assert len(tiles) == sum(-(-n // 4096) for n in numel)
-        assert all(c == 4096 for _, _, c in tiles[:nfull])
-        assert all(0 < c < 4096 for _, _, c in tiles[nfull:])
-        covered = {}
-        for t, off, c in tiles:
-            assert 0 <= t < len(numel) and off % 4096 == 0 and off + c <= numel[t]
-            covered.setdefault(t, []).append((off, c))
-        for t, n in enumerate(numel):
-            pieces = sorted(covered.get(t, []))
-            assert sum(c for _, c in pieces) == n
-            assert [o for o, _ in pieces] == list(range(0, n, 4096))
-        # full tiles keep list order, partial tiles too
-        assert [t for t, _, _ in tiles[:nfull]] == sorted(t for t, _, _ in tiles[:nfull])
-        assert [t for t, _, _ in tiles[nfull:]] == sorted(t for t, _, _ in tiles[nfull:])
+    assert [dppf.sweep_tile_elems(M) for M in (1, 4, 7, 8, 16, 17, 39, 40, 1024)] == \
+        [4096, 4096, 4096, 2048, 2048, 1024, 1024, 4096, 4096]
+    assert lib.dppf_sweep_tile_elems(0) == -1 and lib.dppf_sweep_tile_elems(1025) == -1
+    for tile in (4096, 2048, 1024):
+        for numel in lists:
+            d, nfull, tiles = dppf.layout_tiles(numel, tile)
+            assert d == sum(numel)
+            assert nfull == sum(n // tile for n in numel)
+            assert len(tiles) == sum(-(-n // tile) for n in numel)
+            assert all(c == tile for _, _, c in tiles[:nfull])
+            assert all(0 < c < tile for _, _, c in tiles[nfull:])
+            covered = {}
+            for t, off, c in tiles:
+                assert 0 <= t < len(numel) and off % tile == 0 and off + c <= numel[t]
+                covered.setdefault(t, []).append((off, c))
+            for t, n in enumerate(numel):
+                pieces = sorted(covered.get(t, []))
+                assert sum(c for _, c in pieces) == n
+                assert [o for o, _ in pieces] == list(range(0, n, tile))
+            # full tiles keep list order, partial tiles too
+            assert [t for t, _, _ in tiles[:nfull]] == sorted(t for t, _, _ in tiles[:nfull])
+            assert [t for t, _, _ in tiles[nfull:]] == sorted(t for t, _, _ in tiles[nfull:])
     import ctypes
     bad = (ctypes.c_int64 * 2)(5, -1)
     out = ctypes.c_int64()
-    assert lib.dppf_layout_tiles(2, bad, ctypes.byref(out), ctypes.byref(out), ctypes.byref(out), 0, None, None,
+    assert lib.dppf_layout_tiles(4096, 2, bad, ctypes.byref(out), ctypes.byref(out), ctypes.byref(out), 0, None, None,
                                  None) == -1
-    assert lib.dppf_layout_tiles(1, None, ctypes.byref(out), ctypes.byref(out), ctypes.byref(out), 0, None, None,
+    assert lib.dppf_layout_tiles(4096, 1, None, ctypes.byref(out), ctypes.byref(out), ctypes.byref(out), 0, None, None,
+                                 None) == -1
+    assert lib.dppf_layout_tiles(0, 2, bad, ctypes.byref(out), ctypes.byref(out), ctypes.byref(out), 0, None, None,
                                  None) == -1

@@ -6,7 +6,7 @@ push-only property ||x_m+ - x_m|| = lambda that holds at any size."""
 import numpy as np
 import pytest
 
-from parity import (O, assert_params_close, assert_rel, assert_update_close, download_rows, f32,
+from parity import (O, assert_average_norm, assert_params_close, assert_rel, assert_update_close, download_rows, f32,
                     oracle_local_steps, upload_tensors)
 
 pytestmark = pytest.mark.gpu
@@ -83,11 +83,13 @@ def test_config(name, fused):
             plan.round(xt, vt, gt, lr, mu, wd, pull, push, r_out=r, c_out=c)
         else:
             plan.pull_push_round(xt, pull, push, r_out=r, c_out=c)
-        ref_x, ref_r, ref_c, _ = O.pull_push_round(x_pre, pull, push)
+        ref_x, ref_r, ref_c, ref_avg = O.pull_push_round(x_pre, pull, push)
         got = download_rows(x)
         print(f"  pull={pull:.3g} push={push:.3g}: r gpu {r.cpu().numpy()} oracle {ref_r}", flush=True)
         assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
         assert_rel(c.cpu().numpy(), ref_c, 1e-4, "c")
+        assert_average_norm(plan, ref_avg, "round")
+        del ref_avg
         assert_params_close(got, ref_x, off, spec.tau, "x after the round")
         assert_update_close(got, ref_x, x_pre, "round")
         del ref_x, got

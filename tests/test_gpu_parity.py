@@ -4,8 +4,8 @@ degenerate cases of the method."""
 import numpy as np
 import pytest
 
-from parity import (O, assert_params_close, assert_rel, assert_update_close, download, download_rows, f32,
-                    upload_tensors)
+from parity import (O, assert_average_norm, assert_params_close, assert_rel, assert_update_close, download,
+                    download_rows, f32, upload_tensors)
 
 pytestmark = pytest.mark.gpu
 
@@ -23,7 +23,7 @@ def _hyper(spec):
                 push=f32(spec.push))
 
 
-WORKER_COUNTS = [1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 16, 17, 33]
+WORKER_COUNTS = [1, 2, 3, 4, 5, 6, 7, 8, 9, 11, 16, 17, 24, 33, 39, 40, 45]
 
 
 @pytest.mark.parametrize("M", WORKER_COUNTS)
@@ -63,10 +63,11 @@ def test_round_small_lists(M, misalign):
     assert_params_close(got, ref_new, inp.offsets, 0, "pull_push_round x")
     assert_update_close(got, ref_new, x_host.astype(np.float64), "pull_push_round")
     assert_params_close(download(xbar2)[None], ref_avg[None], inp.offsets, 0, "xbar_out")
+    assert_average_norm(plan, ref_avg, "pull_push_round")
     plan.close()
 
 
-@pytest.mark.parametrize("M", [2, 4, 8, 9, 16, 19])
+@pytest.mark.parametrize("M", [2, 4, 8, 9, 16, 19, 39, 41])
 @pytest.mark.parametrize("wd", [0.0, 1e-3])
 def test_local_step_and_fused_round(M, wd):
     spec = W.small_spec(M=M, seed=200 + M, tau=3, weight_decay=wd)
@@ -101,6 +102,7 @@ def test_local_step_and_fused_round(M, wd):
     assert_params_close(got_v, ref_v, inp.offsets, spec.tau, "fused v")
     assert_params_close(download(xbar)[None], ref_avg[None], inp.offsets, spec.tau, "fused xbar")
     assert_update_close(got_x, ref_x, x_pre, "fused round")
+    assert_average_norm(plan, ref_avg, "fused round")
     assert np.array_equal(download_rows(g), g_before), "gradients were modified"
     plan.close()
 
@@ -380,7 +382,7 @@ def test_on_demand_tail_is_reproducible_and_leaves_its_counter_clean():
     # counter as the previous launch left it.
     shapes = ((3_000_000,), (1_234_567,), (2_000_003,), (777,))
     spec = W.small_spec(M=2, seed=91, shapes=shapes)
-    _, nfull, _ = dppf.layout_tiles(spec.numel)
+    _, nfull, _ = dppf.layout_tiles(spec.numel, dppf.sweep_tile_elems(2))
     cus = torch.cuda.get_device_properties(0).multi_processor_count
     assert nfull >= 4 * cus, "the list must be long enough for the on-demand part of the walk"
     h = _hyper(spec)

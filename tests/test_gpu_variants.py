@@ -3,8 +3,8 @@ consensus variable), the AdamW local step, the logged by-products, and a multi-r
 import numpy as np
 import pytest
 
-from parity import (EPS32, O, assert_params_close, assert_rel, assert_update_close, download, download_rows, f32,
-                    upload_tensors)
+from parity import (EPS32, O, assert_average_norm, assert_params_close, assert_rel, assert_update_close, download,
+                    download_rows, f32, upload_tensors)
 
 pytestmark = pytest.mark.gpu
 
@@ -17,7 +17,7 @@ def _rows(inp, arrays, misalign=0):
     return [upload_tensors(a, inp.offsets, misalign) for a in arrays]
 
 
-@pytest.mark.parametrize("M", [2, 3, 4, 5, 8, 9, 12, 17, 34])
+@pytest.mark.parametrize("M", [2, 3, 4, 5, 8, 9, 12, 17, 34, 39, 40, 47])
 def test_exact_two_term_round(M):
     spec = W.small_spec(M=M, seed=300 + M)
     inp = W.make_inputs(spec)
@@ -34,6 +34,7 @@ def test_exact_two_term_round(M):
     assert_rel(c.cpu().numpy(), pull - (push_r / M) / ref_r, 1e-4, "c")
     assert_params_close(got, ref_x, inp.offsets, 0, "exact round x")
     assert_update_close(got, ref_x, x_host.astype(np.float64), "exact round")
+    assert_average_norm(plan, ref_avg, "exact round")
     # the exact gradient preserves the average of the workers
     mean_err = np.max(np.abs(got.astype(np.float64).mean(axis=0) - ref_avg))
     assert mean_err <= 4 * EPS32 * np.max(np.abs(ref_avg))
@@ -63,7 +64,7 @@ def test_exact_round_zero_distance_worker():
     plan.close()
 
 
-@pytest.mark.parametrize("M", [2, 4, 7, 8, 9, 11, 16, 17, 36])
+@pytest.mark.parametrize("M", [2, 4, 7, 8, 9, 11, 16, 17, 36, 43])
 @pytest.mark.parametrize("push_from", ["average", "consensus"])
 def test_pull_then_push_with_supplied_consensus(M, push_from):
     spec = W.small_spec(M=M, seed=400 + M)
@@ -135,7 +136,7 @@ def test_adamw_local_step(M):
     plan.close()
 
 
-@pytest.mark.parametrize("M", [2, 4, 8, 9, 16, 18])
+@pytest.mark.parametrize("M", [2, 4, 8, 9, 16, 18, 39, 42])
 def test_fused_adamw_round(M):
     # the ViT runs of the paper: AdamW local steps, then the pull-push round
     spec = W.small_spec(M=M, seed=520 + M)
@@ -160,10 +161,11 @@ def test_fused_adamw_round(M):
     s2 = [[t.clone() for t in row] for row in m2]
     plan.round_adamw(x, m1, m2, g, lr, b1, b2, eps, wd, 3, pull, push, r_out=r, c_out=c)
     x_pre, ao, so = O.local_adamw_step(xo, ao, so, np.stack(gk), lr, b1, b2, eps, wd, 3)
-    ref_x, ref_r, ref_c, _ = O.pull_push_round(x_pre, pull, push)
+    ref_x, ref_r, ref_c, ref_avg = O.pull_push_round(x_pre, pull, push)
     got = download_rows(x)
     assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
     assert_rel(c.cpu().numpy(), ref_c, 1e-4, "c")
+    assert_average_norm(plan, ref_avg, "fused adamw round")
     assert_params_close(got, ref_x, inp.offsets, 6, "x", c=ref_c)
     assert_params_close(download_rows(m1), ao, inp.offsets, 6, "m1")
     assert_params_close(download_rows(m2), so, inp.offsets, 6, "m2")
@@ -206,14 +208,14 @@ def test_local_steps_take_full_tiles_in_pairs(M, shapes):
 LONG_SHAPES = ((2_500_000,), (1_234_567,), (1_000_003,), (777,))
 
 
-@pytest.mark.parametrize("M", [2, 12, 17])
+@pytest.mark.parametrize("M", [2, 12, 17, 40])
 def test_every_entry_point_on_a_list_with_an_on_demand_tail(M):
     # With four or more tiles per thread block the read-write sweeps hand the tail of their tiles
     # out on demand; every entry point must give the oracle's result through that path too
     # (M = 12: half a tile per pass, registers beyond the first 256; M = 17: the staged kernels for
     # more workers than fit in registers).
     spec = W.small_spec(M=M, seed=950 + M, shapes=LONG_SHAPES)
-    _, nfull, _ = dppf.layout_tiles(spec.numel)
+    _, nfull, _ = dppf.layout_tiles(spec.numel)      # the largest tiles any kernel uses
     assert nfull >= 4 * torch.cuda.get_device_properties(0).multi_processor_count
     inp = W.make_inputs(spec)
     gk = inp.grads(0)
@@ -303,13 +305,22 @@ def test_round_statistics_and_schedule():
     M = 5
     r_host = np.array([5.0, 5.0, 8.0, 0.0, 1.5], np.float32)
     r = torch.from_numpy(r_host).cuda()
-    out = torch.zeros(2 * M + 1, device="cuda")
+    out = torch.full((2 * M + 3,), -7.0, device="cuda")
     dppf.round_statistics(r, M, f32(0.5), f32(2.0), out)
     st = O.round_statistics(r_host, f32(0.5), f32(2.0))
     got = out.cpu().numpy()
     assert_rel(got[0], st["relaxed_mv"], 1e-6, "relaxed MV")
     assert_rel(got[1:M + 1], st["pull_strength"], 1e-6, "pull strength")
-    assert_rel(got[M + 1:], st["push_strength"], 1e-6, "push strength")
+    assert_rel(got[M + 1:2 * M + 1], st["push_strength"], 1e-6, "push strength")
+    assert np.all(got[2 * M + 1:] == -7.0), "without the norm of the average the last two slots stay untouched"
+    # with the norm of the average (here a made-up value on the device)
+    x_avg = np.array([3.0, -4.0, 12.0])
+    na = torch.tensor([13.0], device="cuda")
+    dppf.round_statistics(r, M, f32(0.5), f32(2.0), out, avg_norm=na)
+    st = O.round_statistics(r_host, f32(0.5), f32(2.0), x_avg=x_avg)
+    got = out.cpu().numpy()
+    assert_rel(got[2 * M + 1], st["average_norm"], 1e-6, "norm of the average")
+    assert_rel(got[2 * M + 2], st["width_over_norm"], 1e-6, "valley width over norm")
     for kind in ("fixed", "decreasing", "increasing"):
         for t in (0, 1, 250, 777, 1000):
             assert abs(dppf.push_schedule(kind, f32(0.5), t, 1000) - O.push_schedule(kind, f32(0.5), t, 1000)) < 1e-7
@@ -376,12 +387,13 @@ def test_alg1_loop_matches_the_oracle(schedule):
             assert did_round
             rounds += 1
             lam = f32(O.push_schedule(schedule, push, t + 1, iters))
-            xo, vo, ro, co, _ = O.dppf_round(xo, vo, gk, lr, mu, wd, pull, lam)
-            mv, pull_strength, push_strength = loop.round_statistics()
-            st = O.round_statistics(ro, pull, lam)
+            xo, vo, ro, co, xa = O.dppf_round(xo, vo, gk, lr, mu, wd, pull, lam)
+            mv, pull_strength, push_strength, avg_norm = loop.round_statistics()
+            st = O.round_statistics(ro, pull, lam, x_avg=xa)
             assert_rel(mv, st["relaxed_mv"], 1e-4, "relaxed MV")
             assert_rel(pull_strength, st["pull_strength"], 1e-4, "pull strength")
             assert abs(push_strength - lam) <= 1e-7
+            assert_rel(avg_norm, st["average_norm"], 1e-4, "norm of the average")
         else:
             assert not did_round
             xo, vo = O.local_sgd_step(xo, vo, gk, lr, mu, wd)
