@@ -81,7 +81,7 @@ int64_t dppf_plan_dim(const dppf_plan* plan);
 /* HOST-ONLY, need no GPU: the work decomposition.  Every tensor is cut into tiles of at most
  * tile_elems consecutive elements; the list holds all full tiles first (in list order), then the
  * partial ones (tensor tails, small tensors).  The sweeps of the round use tiles of
- * dppf_sweep_tile_elems(M) elements (4096 up to 7 workers, 2048 up to 16, 1024 up to 39, 4096
+ * dppf_sweep_tile_elems(M) elements (4096 up to 4 workers, 2048 up to 16, 1024 up to 39, 4096
  * beyond); the local steps always use DPPF_STEP_TILE_ELEMS.  dppf_layout_tiles writes d = sum
  * numel, the number of full tiles and the total; if the three tile arrays are non-NULL (capacity
  * `cap` entries, else DPPF_ELIMIT) also each tile's tensor index, first element inside that

@@ -194,7 +194,7 @@ AdamHyper adam_hyper(float lr, float beta1, float beta2, float eps, float wd, lo
 // partial sums are too many for every block to re-reduce them itself.
 int update_in_registers(dppf_plan* p, int timing_id, const void** xd, const void** vd, bool step, float lr,
                         int nparts, float pull, float push, float* r_out, float* c_out, hipStream_t s) {
-  const bool fold = fold_pays(p, nparts);
+  const bool fold = fold_pays(nparts);
   int rc;
   if (!fold && (rc = launch_finalize(p, nparts, pull, push, true, true, r_out, c_out, s))) return rc;
   DPPF_TIMED(p, timing_id, s, launch_update(p, xd, vd, step, fold, lr, nparts, pull, push, r_out, c_out, s));
@@ -416,7 +416,7 @@ int dppf_plan_create(dppf_plan** out, int M, int T, const int64_t* numel) {
                            hipMemcpyHostToDevice));
     }
     PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->partials),
-                       static_cast<size_t>(p->partials_rows) * p->pstride() * sizeof(double)));
+                       static_cast<size_t>(p->partials_rows) * p->cols() * sizeof(double)));
     PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->coef), static_cast<size_t>(M) * sizeof(Coef)));
     PLAN_TRY(hipMalloc(reinterpret_cast<void**>(&p->avg_norm), sizeof(float)));
     PLAN_TRY(hipMemset(p->avg_norm, 0, sizeof(float)));

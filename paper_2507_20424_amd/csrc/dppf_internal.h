@@ -78,7 +78,9 @@ struct dppf_plan {
   // streaming kernels); `sweep` holds tiles of sweep_tile_elems(M) elements (the sweeps that take
   // all workers of a tile together).  They are the same list when the two sizes agree.
   dppf_detail::TileList step, sweep;
-  double* partials = nullptr;   // [partials_rows][M + 1]: one row per block, then one per on-demand tile
+  // partial sums, stored column by column: [M + 1][partials_rows]; one row per block, then one per
+  // on-demand item of the reducing launch
+  double* partials = nullptr;
   int partials_rows = 0;
   dppf_walk::Sched* sched = nullptr;   // the counter behind the on-demand part of a kernel's tile walk
   dppf_detail::Coef* coef = nullptr;   // [M]
@@ -93,7 +95,7 @@ struct dppf_plan {
   std::vector<dppf_detail::TimingRec> recs;
   std::vector<hipEvent_t> event_pool;
 
-  int pstride() const { return M + 1; }
+  int cols() const { return M + 1; }   // columns of the partial sums: the M squared distances, ||x_A||^2
 };
 
 namespace dppf_detail {
@@ -208,7 +210,7 @@ int launch_step_reduce(dppf_plan* p, const void** xp, const void** vp, const voi
 int launch_update(dppf_plan* p, const void** xp, const void** vp, bool step, bool fold, float lr, int nparts,
                   float pull, float push, float* r_out, float* c_out, hipStream_t s);
 // whether reading `nparts` rows in every block of sweep 2 is still cheaper than a finalize launch
-bool fold_pays(const dppf_plan* p, int nparts);
+bool fold_pays(int nparts);
 int launch_update_exact(dppf_plan* p, const void** xp, int nparts, float pull, float push_r, float* r_out,
                         float* c_out, hipStream_t s);
 // dppf_launch_seq.hip -- M <= 16, Alg. 1 literally; from_consensus: push away from x_C, else from x_A

@@ -34,13 +34,14 @@ constexpr int kMaxLdsM = 39;                  // worker counts with an LDS-stage
 constexpr int kAnyChunk = 4;                  // workers whose loads the any-M kernels keep in flight together
 constexpr int kMaxBlocksPerCU = 8;            // upper bound on resident blocks per CU (sizes buffers)
 
-// Elements of ONE worker's tensor per tile.  What a block holds of a tile grows with M, and from 8
-// workers on half-size tiles are faster (M = 8: +3 %, 12: +6 %, 16: +7 % on the fused round); below
-// that they are slower (M = 4: -4 %).  The LDS-staged kernels hold one vector per lane.  The
-// kernels that take one worker at a time and the any-M streaming kernels use kStepTileElems.
+// Elements of ONE worker's tensor per tile.  What a block holds of a tile grows with M, and from 5
+// workers on half-size tiles are faster (fused round, M = 5: +1 %, 7: +4 %, 8: +6 %, 12: +6 %,
+// 16: +7 %; sweep 2 gains most); up to 4 workers they are slower (M = 4: -7 %, M = 2: -16 %).
+// The LDS-staged kernels hold one vector per lane.  The kernels that take one worker at a time and
+// the any-M streaming kernels use kStepTileElems.
 constexpr int kStepTileElems = 4096;
 constexpr int kLdsTileElems = 4 * kBlock;
-constexpr int kSmallTileFromM = 8;
+constexpr int kSmallTileFromM = 5;
 constexpr int sweep_tile_elems(int M) {
   return M < kSmallTileFromM ? 4096 : (M <= kMaxTemplM ? 2048 : (M <= kMaxLdsM ? kLdsTileElems : kStepTileElems));
 }
@@ -71,7 +72,8 @@ constexpr int kTilesPerWorkerItem = 2;
 
 // What the LDS-staged first sweep folds in.  OPT: 0 = x as it is, 1 = momentum-SGD step (v stored,
 // stepped x kept only on chip), 2 = AdamW step (m1, m2 and the stepped x stored).
-constexpr int kLdsChunk = 4;                  // workers per register chunk of the LDS-staged kernels
+constexpr int kLdsChunk = 4;                  // workers per register chunk of the LDS-staged kernels (8 is no
+                                              // faster and wastes more load slots when M is not a multiple)
 struct LdsOptArgs {
   float* const* vp;          // SGD: momentum; AdamW: first moment
   float* const* sp;          // AdamW: second moment
@@ -195,11 +197,13 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// Block-wide sums of C per-lane doubles; thread c < C writes the c-th sum to out[c].  The per-lane
+// Block-wide sums of C per-lane doubles; thread c < C writes the c-th sum to out[c * stride] (the
+// partial sums are stored column by column: column c of row r sits at [c * rows + r], so that the
+// readers, which add up one column over all rows, read consecutive addresses).  The per-lane
 // values are set back to zero.  May be called repeatedly by a block, with at least one barrier
 // between two calls (the on-demand part of a walk has one per item).
 template <int C>
-__device__ __forceinline__ void block_sums_flush(double (&acc)[C], double* out) {
+__device__ __forceinline__ void block_sums_flush(double (&acc)[C], double* out, int stride) {
   __shared__ double lds[kWaves][C];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
@@ -213,7 +217,7 @@ __device__ __forceinline__ void block_sums_flush(double (&acc)[C], double* out) 
     double s = 0.0;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) s += lds[w][threadIdx.x];
-    out[threadIdx.x] = s;
+    out[static_cast<size_t>(threadIdx.x) * stride] = s;
   }
 }
 
@@ -233,7 +237,52 @@ struct ColumnSums {
     const float s = wave_sum(v);
     if ((threadIdx.x & 63) == 0) acc[(threadIdx.x >> 6) * cols + col] += static_cast<double>(s);
   }
-  __device__ __forceinline__ void flush(double* out) {
+  // G values per lane for the columns col0 .. col0+G-1 (those below `limit` are kept): the wave
+  // sums of all G columns in log2(G) + ... exchanges instead of G full butterflies.  Each exchange
+  // halves the number of columns a lane is responsible for -- the lanes with the exchanged lane bit
+  // set keep the upper half -- until every lane holds one column; three more exchanges finish the
+  // sum over the lanes that share it.  G = 4 or 8.
+  template <int G>
+  __device__ __forceinline__ void add_group(float (&p)[G], int col0, int limit) {
+    static_assert(kAnyChunk == 4 && (G == 4 || G == 8), "group of 4 or 8 columns");
+    const int lane = threadIdx.x & 63;
+    float q[4], r[2], t;
+    if (G == 8) {
+      const bool up = (lane & 32) != 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float mine = up ? p[k + 4] : p[k];
+        const float theirs = up ? p[k] : p[k + 4];
+        q[k] = mine + __shfl_xor(theirs, 32, 64);
+      }
+    } else {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) q[k] = p[k] + __shfl_xor(p[k], 32, 64);
+    }
+    {
+      const bool up = (lane & 16) != 0;
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const float mine = up ? q[k + 2] : q[k];
+        const float theirs = up ? q[k] : q[k + 2];
+        r[k] = mine + __shfl_xor(theirs, 16, 64);
+      }
+    }
+    {
+      const bool up = (lane & 8) != 0;
+      const float mine = up ? r[1] : r[0];
+      const float theirs = up ? r[0] : r[1];
+      t = mine + __shfl_xor(theirs, 8, 64);
+    }
+    t += __shfl_xor(t, 4, 64);
+    t += __shfl_xor(t, 2, 64);
+    t += __shfl_xor(t, 1, 64);
+    // the column this lane ended up with: lane bit 5 chose between halves of 8, bit 4 of 4, bit 3 of 2
+    const int col = col0 + (G == 8 ? ((lane >> 5) & 1) * 4 : 0) + ((lane >> 4) & 1) * 2 + ((lane >> 3) & 1);
+    const bool writer = (lane & 7) == 0 && (G == 8 || (lane & 32) == 0);
+    if (writer && col < limit) acc[(threadIdx.x >> 6) * cols + col] += static_cast<double>(t);
+  }
+  __device__ __forceinline__ void flush(double* out, int stride) {
     __syncthreads();
     for (int c = threadIdx.x; c < cols; c += kBlock) {
       double s = 0.0;
@@ -242,7 +291,7 @@ struct ColumnSums {
         s += acc[w * cols + c];
         acc[w * cols + c] = 0.0;
       }
-      out[c] = s;
+      out[static_cast<size_t>(c) * stride] = s;
     }
     __syncthreads();
   }
@@ -378,7 +427,7 @@ __global__ __launch_bounds__(kBlock) void k_sweep1(const Tile* __restrict__ tile
                                                    const float* const* __restrict__ gp,
                                                    float* const* __restrict__ xbarp, float lr,
                                                    float mu, float wd, double* __restrict__ partials,
-                                                   int pstride, int keep_from) {
+                                                   int prows, int keep_from) {
   double acc[M + 1];
 #pragma unroll
   for (int m = 0; m <= M; ++m) acc[m] = 0.0;
@@ -404,24 +453,29 @@ __global__ __launch_bounds__(kBlock) void k_sweep1(const Tile* __restrict__ tile
                                                          acc);
       },
       [&](int row) {
-        if (NORMS) block_sums_flush<M + 1>(acc, partials + static_cast<size_t>(row) * pstride);
+        if (NORMS) block_sums_flush<M + 1>(acc, partials + row, prows);
       });
 }
 
 // ------------------------------------------------------- partial sums -> r_m and c_m (Eq. 5)
 // One block per column of the partial sums; fixed summation order, fp64.  Columns 0..M-1 are the
 // workers' squared distances, column M is the squared norm of the average.
-__global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ partials, int nparts,
-                                                     int pstride, int M, float pull, float push,
-                                                     Coef* __restrict__ coef, float* __restrict__ r_out,
-                                                     float* __restrict__ c_out, float* __restrict__ avg_norm_out) {
-  __shared__ double lds[kBlock];
+constexpr int kFinalizeThreads = 1024;
+__global__ __launch_bounds__(kFinalizeThreads) void k_finalize(const double* __restrict__ partials, int nparts,
+                                                               int prows, int M, float pull, float push,
+                                                               Coef* __restrict__ coef, float* __restrict__ r_out,
+                                                               float* __restrict__ c_out,
+                                                               float* __restrict__ avg_norm_out) {
+  __shared__ double lds[kFinalizeThreads];
   const int m = blockIdx.x;
+  const double* column = partials + static_cast<size_t>(m) * prows;
   double s = 0.0;
-  for (int b = threadIdx.x; b < nparts; b += kBlock) s += partials[static_cast<size_t>(b) * pstride + m];
+  // a column is contiguous; eight loads are in flight per thread, the additions keep their order
+#pragma unroll 8
+  for (int b = threadIdx.x; b < nparts; b += kFinalizeThreads) s += column[b];
   lds[threadIdx.x] = s;
   __syncthreads();
-  for (int off = kBlock / 2; off > 0; off >>= 1) {
+  for (int off = kFinalizeThreads / 2; off > 0; off >>= 1) {
     if (threadIdx.x < off) lds[threadIdx.x] += lds[threadIdx.x + off];
     __syncthreads();
   }
@@ -449,7 +503,7 @@ __global__ __launch_bounds__(kBlock) void k_finalize(const double* __restrict__ 
 // add the per-block partial sums of sweep 1 in the same fixed order, so all get the same bits.
 template <int M>
 __device__ __forceinline__ void coefficients_from_partials(const double* __restrict__ partials, int nparts,
-                                                           int pstride, float pull, float push,
+                                                           int prows, float pull, float push,
                                                            float (&c)[M], bool (&skip)[M],
                                                            float (&inv_r)[M],
                                                            float* __restrict__ r_out,
@@ -463,10 +517,12 @@ __device__ __forceinline__ void coefficients_from_partials(const double* __restr
   double acc[M + 1];
 #pragma unroll
   for (int m = 0; m <= M; ++m) acc[m] = 0.0;
+  // columns are contiguous; four rows' loads are in flight per thread, the additions keep their order
+#pragma unroll 4
   for (int b = threadIdx.x; b < nparts; b += kBlock) {
 #pragma unroll
-    for (int m = 0; m < M; ++m) acc[m] += partials[static_cast<size_t>(b) * pstride + m];
-    if (want_avg) acc[M] += partials[static_cast<size_t>(b) * pstride + M];
+    for (int m = 0; m < M; ++m) acc[m] += partials[static_cast<size_t>(m) * prows + b];
+    if (want_avg) acc[M] += partials[static_cast<size_t>(M) * prows + b];
   }
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
@@ -566,7 +622,7 @@ __global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tile
                                                    const float* const* __restrict__ vp, float lr,
                                                    const Coef* __restrict__ coef,
                                                    const double* __restrict__ partials, int nparts,
-                                                   int pstride, float pull, float push,
+                                                   int prows, float pull, float push,
                                                    float* __restrict__ r_out, float* __restrict__ c_out,
                                                    float* __restrict__ avg_norm_out) {
   float c[M];
@@ -574,7 +630,7 @@ __global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tile
   if (FOLD) {
     float inv_r[M];
     bool on_average[M];
-    coefficients_from_partials<M>(partials, nparts, pstride, pull, push, c, on_average, inv_r, r_out, c_out,
+    coefficients_from_partials<M>(partials, nparts, prows, pull, push, c, on_average, inv_r, r_out, c_out,
                                   avg_norm_out);
 #pragma unroll
     for (int m = 0; m < M; ++m) skip |= on_average[m] ? (1u << m) : 0u;
@@ -643,12 +699,12 @@ template <int M, int U>
 __global__ __launch_bounds__(kBlock) void k_update_exact(const Tile* __restrict__ tiles, const Walk w, int T,
                                                          float* const* __restrict__ xp,
                                                          const double* __restrict__ partials, int nparts,
-                                                         int pstride, float pull, float push_over_m, float k2,
+                                                         int prows, float pull, float push_over_m, float k2,
                                                          float* __restrict__ r_out, float* __restrict__ c_out,
                                                          float* __restrict__ avg_norm_out) {
   float c[M], inv_r[M];
   bool skip[M];
-  coefficients_from_partials<M>(partials, nparts, pstride, pull, push_over_m, c, skip, inv_r, r_out, c_out,
+  coefficients_from_partials<M>(partials, nparts, prows, pull, push_over_m, c, skip, inv_r, r_out, c_out,
                                 avg_norm_out);
   const float inv_m = 1.0f / static_cast<float>(M);
   walk<true>(
@@ -713,7 +769,7 @@ template <int M, int U, int REF>
 __global__ __launch_bounds__(kBlock) void k_seq1(const Tile* __restrict__ tiles, const Walk w, int T,
                                                  float* const* __restrict__ xp,
                                                  const float* const* __restrict__ xcp, float pull, float keep,
-                                                 double* __restrict__ partials, int pstride) {
+                                                 double* __restrict__ partials, int prows) {
   double acc[M + 1];          // column M (the norm of the average) is not formed here: stays zero
   float scale[M];
 #pragma unroll
@@ -726,7 +782,7 @@ __global__ __launch_bounds__(kBlock) void k_seq1(const Tile* __restrict__ tiles,
       [&](int t) {
         seq_tile<M, U, REF, false, false>(tiles[w.nfull + t], T, xp, xcp, pull, keep, scale, inv_m, acc);
       },
-      [&](int row) { block_sums_flush<M + 1>(acc, partials + static_cast<size_t>(row) * pstride); });
+      [&](int row) { block_sums_flush<M + 1>(acc, partials + row, prows); });
 }
 
 template <int M, int U, int REF>
@@ -734,11 +790,11 @@ __global__ __launch_bounds__(kBlock) void k_seq2(const Tile* __restrict__ tiles,
                                                  float* const* __restrict__ xp,
                                                  const float* const* __restrict__ xcp, float pull, float keep,
                                                  float push, const double* __restrict__ partials, int nparts,
-                                                 int pstride, float* __restrict__ r_post_out) {
+                                                 int prows, float* __restrict__ r_post_out) {
   // lambda / r_m from the partial sums (c = 0 - push/r, so scale = -c; zero distance: no push)
   float c[M], scale[M], inv_r[M];
   bool skip[M];
-  coefficients_from_partials<M>(partials, nparts, pstride, 0.f, push, c, skip, inv_r, r_post_out, nullptr, nullptr);
+  coefficients_from_partials<M>(partials, nparts, prows, 0.f, push, c, skip, inv_r, r_post_out, nullptr, nullptr);
 #pragma unroll
   for (int m = 0; m < M; ++m) scale[m] = skip[m] ? 0.f : -c[m];
   double unused[M + 1];
@@ -894,7 +950,7 @@ __global__ __launch_bounds__(kBlock) void k_adamw_reduce(const Tile* __restrict_
                                                          float* const* __restrict__ ap,
                                                          float* const* __restrict__ sp,
                                                          const float* const* __restrict__ gp, const AdamHyper hp,
-                                                         double* __restrict__ partials, int pstride) {
+                                                         double* __restrict__ partials, int prows) {
   double acc[M + 1];
 #pragma unroll
   for (int m = 0; m <= M; ++m) acc[m] = 0.0;
@@ -902,7 +958,7 @@ __global__ __launch_bounds__(kBlock) void k_adamw_reduce(const Tile* __restrict_
   walk<false>(
       w, 1, [&](int t) { adamw_reduce_tile<M, U, true>(tiles[t], T, xp, ap, sp, gp, hp, inv_m, acc); },
       [&](int t) { adamw_reduce_tile<M, U, false>(tiles[w.nfull + t], T, xp, ap, sp, gp, hp, inv_m, acc); },
-      [&](int row) { block_sums_flush<M + 1>(acc, partials + static_cast<size_t>(row) * pstride); });
+      [&](int row) { block_sums_flush<M + 1>(acc, partials + row, prows); });
 }
 
 // ------------------------------------------------ by-products the paper logs every round
@@ -1072,21 +1128,23 @@ __device__ __forceinline__ void norms_any_tile(const Tile tl, int M, int T, floa
           t[k][it] = load4_stream<FULL>(base + e, FULL ? 4 : tl.count - e);
         }
       }
+    float p[kAnyChunk];
 #pragma unroll
-    for (int k = 0; k < kAnyChunk; ++k)
+    for (int k = 0; k < kAnyChunk; ++k) {
+      p[k] = 0.f;
       if (m + k < M) {
-        float p = 0.f;
 #pragma unroll
-        for (int it = 0; it < kAnyVec; ++it) p = sumsq4(t[k][it] - xbar[it], p);   // past a partial tile's end: 0 - 0
-        sums.add(p, m + k);
+        for (int it = 0; it < kAnyVec; ++it) p[k] = sumsq4(t[k][it] - xbar[it], p[k]);   // past a partial tile's end: 0 - 0
       }
+    }
+    sums.add_group<kAnyChunk>(p, m, M);
   }
 }
 
 __global__ __launch_bounds__(kBlock) void k_norms_any(const Tile* __restrict__ tiles, const Walk w, int M, int T,
                                                       float* const* __restrict__ xp,
                                                       const float* const* __restrict__ xbarp,
-                                                      double* __restrict__ partials, int pstride) {
+                                                      double* __restrict__ partials, int prows) {
   extern __shared__ double lds_cols[];
   ColumnSums sums;
   sums.init(lds_cols, M + 1);
@@ -1100,7 +1158,7 @@ __global__ __launch_bounds__(kBlock) void k_norms_any(const Tile* __restrict__ t
         const Tile tl = tiles[w.nfull + t];
         norms_any_tile<false>(tl, M, T, xp, xbarp[tl.tensor] + tl.offset, sums);
       },
-      [&](int row) { sums.flush(partials + static_cast<size_t>(row) * pstride); });
+      [&](int row) { sums.flush(partials + row, prows); });
 }
 
 // ------------------------------- Eq. 5 (EXACT = false) or Eq. 4 (a) (EXACT = true) with the average
@@ -1255,22 +1313,24 @@ __device__ __forceinline__ void seq_any_tile(const Tile tl, int M, int T, float*
                            : load4<FULL>(base + e, FULL ? 4 : tl.count - e);
         }
       }
+    float p[kAnyChunk];
 #pragma unroll
-    for (int k = 0; k < kAnyChunk; ++k)
+    for (int k = 0; k < kAnyChunk; ++k) {
+      p[k] = 0.f;
       if (m + k < M) {
         float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
         const float scale = WRITE ? (coef[m + k].skip != 0 ? 0.f : -coef[m + k].c) : 0.f;
-        float p = 0.f;
 #pragma unroll
         for (int it = 0; it < kAnyVec; ++it) {
           const int e = 4 * (threadIdx.x + it * kBlock);
           const f4 pulled = fma4(cv[it], pull, t[k][it] * keep);
           const f4 gap = pulled - ref[it];
           if (WRITE) store4_stream<FULL>(base + e, fma4(gap, scale, pulled), FULL ? 4 : tl.count - e);
-          else p = sumsq4(gap, p);       // lanes past a partial tile's end hold zeros throughout
+          else p[k] = sumsq4(gap, p[k]);       // lanes past a partial tile's end hold zeros throughout
         }
-        if (!WRITE) sums.add(p, m + k);
       }
+    }
+    if (!WRITE) sums.add_group<kAnyChunk>(p, m, M);
   }
 }
 
@@ -1280,7 +1340,7 @@ __global__ __launch_bounds__(kBlock) void k_seq_any(const Tile* __restrict__ til
                                                     const float* const* __restrict__ xcp,
                                                     const float* const* __restrict__ refp, float pull, float keep,
                                                     const Coef* __restrict__ coef, double* __restrict__ partials,
-                                                    int pstride) {
+                                                    int prows) {
   extern __shared__ double lds_cols[];
   ColumnSums sums;
   if (!WRITE) sums.init(lds_cols, M + 1);
@@ -1297,7 +1357,7 @@ __global__ __launch_bounds__(kBlock) void k_seq_any(const Tile* __restrict__ til
                                         REF == 2 ? refp[tl.tensor] + tl.offset : nullptr, pull, keep, coef, sums);
       },
       [&](int row) {
-        if (!WRITE) sums.flush(partials + static_cast<size_t>(row) * pstride);
+        if (!WRITE) sums.flush(partials + row, prows);
       });
 }
 
@@ -1307,25 +1367,34 @@ __global__ __launch_bounds__(kBlock) void k_seq_any(const Tile* __restrict__ til
 // chunk is processed), parks every worker's vector in its own LDS column, and once the average is
 // known reads them back.  LDS holds M x 256 vectors (4 KB per worker) and, for the reducing
 // sweep, the per-wave running sums.
+//
+// Two things about the chunk pipeline were measured, not guessed.  (1) Every slot of a chunk
+// issues its loads, also the slots past the last worker (they re-read the last worker and are never
+// consumed): with a fixed number of loads per chunk the compiler can wait for exactly this chunk's
+// data while the next chunk's loads stay in flight; loads under a condition make it wait for
+// everything (the sweep ran 1.5 times longer).  (2) Carrying a chunk across tiles, to request the
+// next tile's first workers before the current tile's second phase, made the generated code slower,
+// not faster (+36 %), with items of one, two or four tiles alike: each tile starts its own pipeline.
 
+// OPT: 0 = x as it is, 1 = momentum-SGD step folded in (v stored, stepped x kept only on chip),
+// 2 = AdamW step folded in (m1, m2 and the stepped x stored); see LdsOptArgs.
 template <int OPT, bool FULL>
 struct LdsChunk {
   f4 x[kLdsChunk], a[kLdsChunk], s[kLdsChunk], g[kLdsChunk];
   __device__ __forceinline__ void load(int m0, int M, int T, const Tile& tl, int e, int n, float* const* xp,
                                        const LdsOptArgs& o) {
 #pragma unroll
-    for (int k = 0; k < kLdsChunk; ++k)
-      if (m0 + k < M) {
-        const size_t slot = static_cast<size_t>(m0 + k) * T + tl.tensor;
-        x[k] = load4_stream<FULL>(xp[slot] + tl.offset + e, n);
-        if (OPT != 0) {
-          a[k] = load4_stream<FULL>(o.vp[slot] + tl.offset + e, n);
-          g[k] = load4_stream<FULL>(o.gp[slot] + tl.offset + e, n);
-        }
-        if (OPT == 2) s[k] = load4_stream<FULL>(o.sp[slot] + tl.offset + e, n);
+    for (int k = 0; k < kLdsChunk; ++k) {
+      const int m = m0 + k < M ? m0 + k : M - 1;
+      const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
+      x[k] = load4_stream<FULL>(xp[slot] + tl.offset + e, n);
+      if (OPT != 0) {
+        a[k] = load4_stream<FULL>(o.vp[slot] + tl.offset + e, n);
+        g[k] = load4_stream<FULL>(o.gp[slot] + tl.offset + e, n);
       }
+      if (OPT == 2) s[k] = load4_stream<FULL>(o.sp[slot] + tl.offset + e, n);
+    }
   }
-  // the k-th worker's x after the folded step (its state is stored on the way)
   __device__ __forceinline__ f4 stepped(int k, int m, int T, const Tile& tl, int e, int n, float* const* xp,
                                         const LdsOptArgs& o) {
     if (OPT == 0) return x[k];
@@ -1340,7 +1409,7 @@ struct LdsChunk {
     adamw_vec(x[k], a[k], s[k], g[k], o.adam, xn, an, sn);
     store4_stream<FULL>(o.vp[slot] + tl.offset + e, an, n);
     store4_stream<FULL>(o.sp[slot] + tl.offset + e, sn, n);
-    store4<FULL>(xp[slot] + tl.offset + e, xn, n);     // read again by sweep 2
+    store4<FULL>(xp[slot] + tl.offset + e, xn, n);
     return first_components<FULL>(xn, n);
   }
 };
@@ -1363,22 +1432,35 @@ __device__ __forceinline__ void sweep1_lds_tile(const Tile tl, int M, int T, flo
         else s += xn - x0;
       }
   };
+  int m0 = 0;
   ca.load(0, M, T, tl, e, n, xp, o);
 #pragma unroll 1
-  for (int m0 = 0; m0 < M; m0 += 2 * kLdsChunk) {
+  for (; m0 + 2 * kLdsChunk < M; m0 += 2 * kLdsChunk) {
     cb.load(m0 + kLdsChunk, M, T, tl, e, n, xp, o);
     consume(ca, m0);
     ca.load(m0 + 2 * kLdsChunk, M, T, tl, e, n, xp, o);
     consume(cb, m0 + kLdsChunk);
   }
+  if (M - m0 > kLdsChunk) {
+    cb.load(m0 + kLdsChunk, M, T, tl, e, n, xp, o);
+    consume(ca, m0);
+    consume(cb, m0 + kLdsChunk);
+  } else {
+    consume(ca, m0);
+  }
   const f4 mo = scale_by_inverse_count(s, M, inv_m);
   const f4 xa = x0 + mo;
   if (XBAR == 1) store4_stream<FULL>(xbarp[tl.tensor] + tl.offset + e, xa, n);
   sums.add(sumsq4(xa, 0.f), M);
-#pragma unroll 4
-  for (int m = 0; m < M; ++m) {
-    const f4 xm = stage[m * kBlock + threadIdx.x];     // this lane's own column: no barrier needed
-    sums.add(sumsq4((xm - x0) - mo, 0.f), m);
+#pragma unroll 1
+  for (int g0 = 0; g0 < M; g0 += 8) {
+    float p[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      p[k] = 0.f;
+      if (g0 + k < M) p[k] = sumsq4((stage[(g0 + k) * kBlock + threadIdx.x] - x0) - mo, 0.f);
+    }
+    sums.add_group<8>(p, g0, M);
   }
 }
 
@@ -1386,7 +1468,7 @@ template <int OPT, int XBAR>
 __global__ __launch_bounds__(kBlock) void k_sweep1_lds(const Tile* __restrict__ tiles, const Walk w, int M, int T,
                                                        float* const* __restrict__ xp, const LdsOptArgs o,
                                                        float* const* __restrict__ xbarp,
-                                                       double* __restrict__ partials, int pstride) {
+                                                       double* __restrict__ partials, int prows) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   f4* stage = reinterpret_cast<f4*>(lds_raw);
   ColumnSums sums;
@@ -1395,7 +1477,7 @@ __global__ __launch_bounds__(kBlock) void k_sweep1_lds(const Tile* __restrict__ 
   walk<false>(
       w, 1, [&](int t) { sweep1_lds_tile<OPT, XBAR, true>(tiles[t], M, T, xp, o, xbarp, inv_m, stage, sums); },
       [&](int t) { sweep1_lds_tile<OPT, XBAR, false>(tiles[w.nfull + t], M, T, xp, o, xbarp, inv_m, stage, sums); },
-      [&](int row) { sums.flush(partials + static_cast<size_t>(row) * pstride); });
+      [&](int row) { sums.flush(partials + row, prows); });
 }
 
 // MODE: 0 = Eq. 5; 1 = Eq. 5 on x - lr v (fused momentum-SGD round: x in memory is still the old
@@ -1408,14 +1490,14 @@ __device__ __forceinline__ void sweep2_lds_tile(const Tile tl, int M, int T, flo
   const int n = FULL ? 4 : tl.count - e;
   f4 x0 = {0.f, 0.f, 0.f, 0.f}, s = {0.f, 0.f, 0.f, 0.f};
   f4 ax[kLdsChunk], av[kLdsChunk], bx[kLdsChunk], bv[kLdsChunk];
-  auto load = [&](f4 (&cx)[kLdsChunk], f4 (&cv)[kLdsChunk], int m0) {
+  auto load = [&](f4 (&cx)[kLdsChunk], f4 (&cv)[kLdsChunk], int m0) {   // unconditional, see above
 #pragma unroll
-    for (int k = 0; k < kLdsChunk; ++k)
-      if (m0 + k < M) {
-        const size_t slot = static_cast<size_t>(m0 + k) * T + tl.tensor;
-        cx[k] = load4_stream<FULL>(xp[slot] + tl.offset + e, n);
-        if (MODE == 1) cv[k] = load4_stream<FULL>(vp[slot] + tl.offset + e, n);
-      }
+    for (int k = 0; k < kLdsChunk; ++k) {
+      const int m = m0 + k < M ? m0 + k : M - 1;
+      const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
+      cx[k] = load4_stream<FULL>(xp[slot] + tl.offset + e, n);
+      if (MODE == 1) cv[k] = load4_stream<FULL>(vp[slot] + tl.offset + e, n);
+    }
   };
   auto consume = [&](f4 (&cx)[kLdsChunk], f4 (&cv)[kLdsChunk], int m0) {
 #pragma unroll
@@ -1427,13 +1509,21 @@ __device__ __forceinline__ void sweep2_lds_tile(const Tile tl, int M, int T, flo
         else s += xn - x0;
       }
   };
+  int m0 = 0;                // two alternating chunks, see sweep1_lds_tile
   load(ax, av, 0);
 #pragma unroll 1
-  for (int m0 = 0; m0 < M; m0 += 2 * kLdsChunk) {
+  for (; m0 + 2 * kLdsChunk < M; m0 += 2 * kLdsChunk) {
     load(bx, bv, m0 + kLdsChunk);
     consume(ax, av, m0);
     load(ax, av, m0 + 2 * kLdsChunk);
     consume(bx, bv, m0 + kLdsChunk);
+  }
+  if (M - m0 > kLdsChunk) {
+    load(bx, bv, m0 + kLdsChunk);
+    consume(ax, av, m0);
+    consume(bx, bv, m0 + kLdsChunk);
+  } else {
+    consume(ax, av, m0);
   }
   const f4 mo = scale_by_inverse_count(s, M, inv_m);
   f4 usum = {0.f, 0.f, 0.f, 0.f};

@@ -31,7 +31,7 @@ int launch_adamw_reduce(dppf_plan* p, const void** xd, const void** ad, const vo
     shape->walk = walk;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->sweep.dev, walk, p->T, (float* const*)(xd),
                        (float* const*)(ad), (float* const*)(sd), (const float* const*)(gd), hp, p->partials,
-                       p->pstride());
+                       p->partials_rows);
   })
   HIP_TRY(hipGetLastError());
   return DPPF_OK;

@@ -29,7 +29,7 @@ int launch_norms_any(dppf_plan* p, const void** xp, const void** xbarp, GridShap
   shape->grid = grid;
   shape->walk = walk;
   hipLaunchKernelGGL(k_norms_any, dim3(grid), dim3(kBlock), lds, s, p->step.dev, walk, p->M, p->T,
-                     (float* const*)(xp), (const float* const*)(xbarp), p->partials, p->pstride());
+                     (float* const*)(xp), (const float* const*)(xbarp), p->partials, p->partials_rows);
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
 }
@@ -76,7 +76,7 @@ int launch_seq_any(dppf_plan* p, const void** xp, const void** xcp, const void**
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), lds, s, p->step.dev, walk, p->M, p->T, (float* const*)(xp),
                      (const float* const*)(xcp), (const float* const*)(refp), pull, keep, p->coef, p->partials,
-                     p->pstride());
+                     p->partials_rows);
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
 }

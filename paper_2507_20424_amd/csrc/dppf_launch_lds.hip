@@ -33,7 +33,7 @@ int launch_sweep1_lds(dppf_plan* p, const void** xp, int opt, const LdsOptArgs& 
   float* const* x = (float* const*)(xp);
   float* const* xb = (float* const*)(xbarp);
   double* parts = p->partials;
-  const int ps = p->pstride();
+  const int ps = p->partials_rows;
   const double bytes = (opt == 0 ? 4.0 : (opt == 1 ? 16.0 : 28.0)) * p->M;
   // a pure read keeps the even split (per-tile sums would cost more than they win), see make_walk's policy
   const OnDemand policy = opt == 0 && !store_avg ? dppf_walk::kEvenSplit : dppf_walk::kOnDemandReducing;

@@ -22,8 +22,8 @@ int launch_finalize(dppf_plan* p, int nparts, float pull, float push, bool want_
                     float* r_out, float* c_out, hipStream_t s) {
   int rc = timing_begin(p, DPPF_K_FINALIZE, s);
   if (rc) return rc;
-  hipLaunchKernelGGL(k_finalize, dim3(p->M + (want_avg_norm ? 1 : 0)), dim3(kBlock), 0, s, p->partials, nparts,
-                     p->pstride(), p->M, pull, push, want_coef ? p->coef : nullptr, r_out, c_out, p->avg_norm);
+  hipLaunchKernelGGL(k_finalize, dim3(p->M + (want_avg_norm ? 1 : 0)), dim3(kFinalizeThreads), 0, s, p->partials, nparts,
+                     p->partials_rows, p->M, pull, push, want_coef ? p->coef : nullptr, r_out, c_out, p->avg_norm);
   HIP_TRY(hipGetLastError());
   return timing_end(p, s);
 }

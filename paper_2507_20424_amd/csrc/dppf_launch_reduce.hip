@@ -23,7 +23,7 @@ int launch(dppf_plan* p, const void** xp, const void** xbarp, KeepPolicy keep, G
       shape->walk = walk;
     }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->sweep.dev, walk, p->T, x, nullptr, nullptr, xb, 0.f,
-                       0.f, 0.f, p->partials, p->pstride(), keep_from_tile(p, keep));
+                       0.f, 0.f, p->partials, p->partials_rows, keep_from_tile(p, keep));
   })
   HIP_TRY(hipGetLastError());
   return DPPF_OK;

@@ -21,7 +21,7 @@ int reduce(dppf_plan* p, const void** xp, const void** xcp, float pull, GridShap
     shape->grid = grid;
     shape->walk = walk;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->sweep.dev, walk, p->T, x, xc, pull, keep,
-                       p->partials, p->pstride());
+                       p->partials, p->partials_rows);
   })
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
@@ -41,7 +41,7 @@ int update(dppf_plan* p, const void** xp, const void** xcp, float pull, float pu
     if (rc) return rc;
     const Walk walk = plan_walk(p, p->sweep, gfull, 1, 1, dppf_walk::kOnDemand, 8.0 * kM + 4.0);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->sweep.dev, walk, p->T, x, xc, pull, keep, push,
-                       p->partials, nparts, p->pstride(), r_post_out);
+                       p->partials, nparts, p->partials_rows, r_post_out);
   })
   HIP_TRY(hipGetLastError());
   return DPPF_OK;

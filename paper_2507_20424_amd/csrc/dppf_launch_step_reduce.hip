@@ -23,7 +23,7 @@ int launch(dppf_plan* p, const void** xp, const void** vp, const void** gp, cons
     shape->grid = grid;
     shape->walk = walk;
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->sweep.dev, walk, p->T, x, v, g, xb, lr, mu, wd,
-                       p->partials, p->pstride(), keep_from_tile(p, kKeepTail));
+                       p->partials, p->partials_rows, keep_from_tile(p, kKeepTail));
   })
   HIP_TRY(hipGetLastError());
   return DPPF_OK;

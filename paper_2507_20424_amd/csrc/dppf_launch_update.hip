@@ -6,9 +6,11 @@ namespace dppf_detail {
 namespace {
 
 // Every block of sweep 2 re-reduces the rows of partial sums itself (no finalize launch on the
-// round's critical path) as long as that is a small read; beyond this many doubles per block a
-// separate finalize launch is cheaper.
-constexpr long long kFoldMaxDoubles = 200000;
+// round's critical path) as long as there are few of them -- an evenly split reducing sweep leaves
+// one row per block.  A sweep that took its tiles on demand leaves a row per tile; re-reading
+// twenty thousand rows in every block costs more than the extra launch (ViT-B-sized list, M = 4:
+// 27 against 8 microseconds).
+constexpr int kFoldMaxRows = 4096;
 
 template <bool STEP, bool FOLD>
 int launch(dppf_plan* p, const void** xp, const void** vp, float lr, int nparts, float pull, float push,
@@ -23,7 +25,7 @@ int launch(dppf_plan* p, const void** xp, const void** vp, float lr, int nparts,
     if (rc) return rc;
     const Walk walk = plan_walk(p, p->sweep, gfull, 1, 1, dppf_walk::kOnDemand, (STEP ? 12.0 : 8.0) * kM);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->sweep.dev, walk, p->T, x, v, lr, p->coef,
-                       p->partials, nparts, p->pstride(), pull, push, r_out, c_out, p->avg_norm);
+                       p->partials, nparts, p->partials_rows, pull, push, r_out, c_out, p->avg_norm);
   })
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
@@ -31,9 +33,7 @@ int launch(dppf_plan* p, const void** xp, const void** vp, float lr, int nparts,
 
 }  // namespace
 
-bool fold_pays(const dppf_plan* p, int nparts) {
-  return static_cast<long long>(nparts) * p->pstride() <= kFoldMaxDoubles;
-}
+bool fold_pays(int nparts) { return nparts <= kFoldMaxRows; }
 
 int launch_update(dppf_plan* p, const void** xp, const void** vp, bool step, bool fold, float lr, int nparts,
                   float pull, float push, float* r_out, float* c_out, hipStream_t s) {
@@ -56,7 +56,7 @@ int launch_update_exact(dppf_plan* p, const void** xp, int nparts, float pull, f
     if (rc) return rc;
     const Walk walk = plan_walk(p, p->sweep, gfull, 1, 1, dppf_walk::kOnDemand, 8.0 * kM);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, p->sweep.dev, walk, p->T, x, p->partials, nparts,
-                       p->pstride(), pull, push_r / mf, push_r / (mf * mf), r_out, c_out, p->avg_norm);
+                       p->partials_rows, pull, push_r / mf, push_r / (mf * mf), r_out, c_out, p->avg_norm);
   })
   HIP_TRY(hipGetLastError());
   return DPPF_OK;
