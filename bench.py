@@ -244,6 +244,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vitb16_M4")
     ap.add_argument("--call", default="round", choices=sorted(CALL_BYTES))
+    ap.add_argument("--workers", type=int, default=0,
+                    help="override the workload's number of workers M (same list, same value scales)")
     ap.add_argument("--graph", action="store_true",
                     help="also time replays of a HIP graph that captured one step (headline and per-config rows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -266,6 +268,9 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     spec = W.SPECS[args.workload]
+    if args.workers > 0 and args.workers != spec.M:
+        import dataclasses
+        spec = dataclasses.replace(spec, name=f"{spec.name}_as_M{args.workers}", M=args.workers)
     f32 = lambda a: float(np.float32(a))  # noqa: E731
     hyper = dict(lr=f32(spec.lr), mu=f32(spec.momentum), wd=f32(spec.weight_decay), pull=f32(spec.pull),
                  push=f32(spec.push))

@@ -187,8 +187,8 @@ inline bool rows_fit(const dppf_plan* p, int grid, const Walk& walk) {
 constexpr int at_most_tile(int u, int M) {
   return u < vectors_per_lane(sweep_tile_elems(M)) ? u : vectors_per_lane(sweep_tile_elems(M));
 }
-constexpr int unroll_plain(int M) { return at_most_tile(M <= 4 ? 4 : (M <= 8 ? 2 : 1), M); }
-constexpr int unroll_step_update(int M) { return at_most_tile(M <= 4 ? 4 : (M <= 8 ? 2 : 1), M); }
+constexpr int unroll_plain(int M) { return at_most_tile(M <= 4 ? 4 : 2, M); }
+constexpr int unroll_step_update(int M) { return at_most_tile(M <= 4 ? 4 : 2, M); }
 constexpr int unroll_fused(int M) { return at_most_tile(M <= 8 ? 4 : 2, M); }
 constexpr int unroll_seq(int M) { return at_most_tile(unroll_plain(M) > 2 ? 2 : unroll_plain(M), M); }
 

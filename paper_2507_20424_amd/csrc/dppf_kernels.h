@@ -571,12 +571,8 @@ __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* 
   constexpr int kVec = vectors_per_lane(sweep_tile_elems(M));
   static_assert(kVec % U == 0, "a lane's vectors of a tile are taken U at a time");
   float* x[M];
-  const float* v[M];
 #pragma unroll
-  for (int m = 0; m < M; ++m) {
-    x[m] = xp[m * T + tl.tensor] + tl.offset;
-    if (STEP) v[m] = vp[m * T + tl.tensor] + tl.offset;
-  }
+  for (int m = 0; m < M; ++m) x[m] = xp[m * T + tl.tensor] + tl.offset;
 #pragma unroll 1
   for (int it = 0; it < kVec / U; ++it) {
     int e[U], n[U];
@@ -592,9 +588,12 @@ __device__ __forceinline__ void sweep2_tile(const Tile tl, int T, float* const* 
 #pragma unroll
       for (int k = 0; k < U; ++k) xv[k][m] = load4_stream<FULL>(x[m] + e[k], n[k]);
       if (STEP) {
+        // v is read once: its pointer is fetched where it is used (kept in an array beside x's, the
+        // 2M pointers ran one instantiation out of scalar registers)
+        const float* vm = vp[m * T + tl.tensor] + tl.offset;
         f4 vv[U];
 #pragma unroll
-        for (int k = 0; k < U; ++k) vv[k] = load4_stream<FULL>(v[m] + e[k], n[k]);
+        for (int k = 0; k < U; ++k) vv[k] = load4_stream<FULL>(vm + e[k], n[k]);
 #pragma unroll
         for (int k = 0; k < U; ++k) xv[k][m] = fma4(vv[k], -lr, xv[k][m]);
       }
@@ -635,10 +634,19 @@ __global__ __launch_bounds__(kBlock) void k_sweep2(const Tile* __restrict__ tile
 #pragma unroll
     for (int m = 0; m < M; ++m) skip |= on_average[m] ? (1u << m) : 0u;
   } else {
+    // through LDS, like the folded form: read straight into scalar registers the M coefficients
+    // compete with the tile's 2M pointers and one instantiation (M = 12) spilled
+    __shared__ float c_sh[M];
+    __shared__ int skip_sh[M];
+    if (threadIdx.x < M) {
+      c_sh[threadIdx.x] = coef[threadIdx.x].c;
+      skip_sh[threadIdx.x] = coef[threadIdx.x].skip;
+    }
+    __syncthreads();
 #pragma unroll
     for (int m = 0; m < M; ++m) {
-      c[m] = coef[m].c;
-      skip |= coef[m].skip != 0 ? (1u << m) : 0u;
+      c[m] = c_sh[m];
+      skip |= skip_sh[m] != 0 ? (1u << m) : 0u;
     }
   }
   const float inv_m = 1.0f / static_cast<float>(M);

@@ -25,3 +25,16 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    # the margins the GPU parity checks were passed with (worst case over the run, per kind of check)
+    try:
+        import parity
+    except Exception:
+        return
+    if not parity.OBSERVED:
+        return
+    terminalreporter.write_sep("-", "worst observed errors of the GPU parity checks")
+    for kind, (value, what, bar) in sorted(parity.OBSERVED.items()):
+        terminalreporter.write_line(f"{kind}: {value:.3e}  ({value / bar:.2%} of the bar; in: {what})")

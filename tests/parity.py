@@ -13,6 +13,11 @@ Tolerances (fp32 kernels against the float64 oracle):
                only for a strong push (|c| of 30..600 at the paper's ImageNet settings applied to
                tightly clustered synthetic workers).  At |c| <= 1 the term is about 1e-6 of the
                tensor's largest element.
+               Where that factor would make the check weak (a strong push, |c| >> 1) the tests ALSO run the
+               plain round on the same float32 inputs -- no local step in front, so both sides start
+               from identical numbers -- and compare the worker's new gap to the average,
+               x_m+ - x_A = (x_m - x_A)(1 - c_m), at relative 1e-5 with no amplification
+               (assert_gap_close).
   r_m, c_m     relative 1e-4
   update       || (gpu x+ - x_pre) - (oracle x+ - x_pre) ||_2 <= 1e-3 || oracle x+ - x_pre ||_2
                so that a wrong or missing push cannot hide inside the parameter tolerance.
@@ -32,6 +37,16 @@ if ROOT not in sys.path:
 from oracle import dppf_oracle as O  # noqa: E402
 
 EPS32 = 2.0 ** -24
+
+# Worst errors seen by the comparison helpers, per kind of check, over the whole test run; the
+# conftest prints them after the run so that the margin against each stated bar stays visible.
+OBSERVED = {}
+
+
+def _record(kind: str, what: str, value: float, bar: float) -> None:
+    worst = OBSERVED.get(kind)
+    if worst is None or value / bar > worst[0] / worst[2]:
+        OBSERVED[kind] = (float(value), what, float(bar))
 
 
 def f32(v: float) -> float:
@@ -112,6 +127,11 @@ def assert_params_close(gpu: np.ndarray, ref: np.ndarray, offsets: np.ndarray, t
         err = np.abs(gpu[m].astype(np.float64) - ref[m])
         amp = 1.0 if c is None else max(1.0, 1.0 + 2.0 * abs(float(c[m])))
         tol = 1e-5 * np.abs(ref[m]) + (4 + 2 * tau) * amp * EPS32 * scale
+        # the stated bar on its own, for the elements that are not near zero (above the tensor's rms)
+        big = (np.abs(ref[m]) >= np.sqrt(np.mean(ref[m] * ref[m]))) & (np.abs(ref[m]) > 0)
+        if big.any():
+            _record("parameters, relative error of elements above rms (bar 1e-5)", what,
+                    float(np.max(err[big] / np.abs(ref[m][big]))), 1e-5)
         bad = err > tol
         if bad.any():
             i = int(np.argmax(err - tol))
@@ -124,6 +144,10 @@ def assert_rel(gpu, ref, rtol: float, what: str):
     ref = np.asarray(ref, dtype=np.float64)
     assert gpu.shape == ref.shape, (what, gpu.shape, ref.shape)
     err = np.abs(gpu - ref)
+    nz = np.abs(ref) > 0
+    if np.any(nz):
+        _record(f"scalars (r, c, ...), relative error (bar {rtol:g})", what, float(np.max(err[nz] / np.abs(ref[nz]))),
+                rtol)
     assert np.all(err <= rtol * np.abs(ref)), f"{what}: gpu {gpu} oracle {ref} rel {err / np.maximum(np.abs(ref), 1e-300)}"
 
 
@@ -134,7 +158,34 @@ def assert_update_close(gpu_new: np.ndarray, ref_new: np.ndarray, x_pre: np.ndar
         if nrm == 0.0:
             continue
         diff = np.linalg.norm((gpu_new[m].astype(np.float64) - x_pre[m]) - upd)
+        _record("update x+ - x, relative L2 error (bar 1e-3)", what, float(diff / nrm), 1e-3)
         assert diff <= 1e-3 * nrm, f"{what}: worker {m} update error {diff / nrm:.3e}"
+
+
+def assert_gap_close(gpu_new: np.ndarray, ref_new: np.ndarray, x_avg: np.ndarray, x_in: np.ndarray,
+                     offsets: np.ndarray, what: str):
+    """The workers' gaps to the (pre-round) average after a round that started from the float32 values
+    x_in on both sides:
+      |gpu gap - oracle gap| <= 1e-5 |oracle gap| + 4 * 2^-24 * max|tensor of x_in| + 1e-6 rms(oracle gap).
+    The floor covers the elements whose gap happens to be near zero: the rounding of x+ itself (its
+    last bit, plus those of the average), and the last bit of the OLD gap times (1 - c) -- one part
+    in 10^7 of the typical new gap, so a millionth of the gaps' rms bounds it whatever the
+    coefficient.  Nothing else is multiplied by the coefficient: a strong push is checked as sharply
+    as a weak one."""
+    scale = per_element_scale(x_in.astype(np.float64), offsets)
+    for m in range(ref_new.shape[0]):
+        ref_gap = ref_new[m] - x_avg
+        err = np.abs((gpu_new[m].astype(np.float64) - x_avg) - ref_gap)
+        tol = 1e-5 * np.abs(ref_gap) + 4 * EPS32 * scale + 1e-6 * np.sqrt(np.mean(ref_gap * ref_gap))
+        big = (np.abs(ref_gap) >= np.sqrt(np.mean(ref_gap * ref_gap))) & (np.abs(ref_gap) > 0)
+        if big.any():
+            _record("gap x+ - x_A after a round on identical inputs, relative error above rms (bar 1e-5)", what,
+                    float(np.max(err[big] / np.abs(ref_gap[big]))), 1e-5)
+        bad = err > tol
+        if bad.any():
+            i = int(np.argmax(err - tol))
+            raise AssertionError(f"{what}: worker {m}, {int(bad.sum())} gaps out of tolerance; worst at {i}: "
+                                 f"err {err[i]:.3e} tol {tol[i]:.3e} gap {ref_gap[i]!r}")
 
 
 def assert_average_norm(plan, x_avg: np.ndarray, what: str):

@@ -357,6 +357,51 @@ def test_many_rounds_driver_tracks_the_oracle_and_the_valley_width():
     plan.close()
 
 
+def test_decaying_learning_rate_settles_the_valley_width_at_push_over_pull():
+    # Theorem 1: the distance of a worker to the average tends to lambda/alpha + O(eta sigma0 + M^-1/2).
+    # With a cosine-decayed learning rate and gradient noise large enough to matter (sigma0 = 0.7,
+    # lambda/alpha = 2) the width first overshoots -- the eta*sigma0 term -- and then closes in on
+    # lambda/alpha as eta goes to zero.  The GPU trajectory is checked against the oracle's all the way.
+    M, d, tau, rounds = 8, 20_000, 4, 60
+    spec = W.small_spec(M=M, seed=901, shapes=((d - 7,), (7,)), tau=tau, sigma_grad=5e-3)
+    inp = W.make_inputs(spec)
+    lr0, mu, wd, pull, push = 0.1, f32(0.9), 0.0, f32(0.25), f32(0.5)
+    sigma0 = spec.sigma_grad * np.sqrt(d)
+    plan = dppf.Plan(M, spec.numel)
+    x, v = _rows(inp, inp.x), _rows(inp, inp.v)
+    xo, vo = np.stack(inp.x).astype(np.float64), np.stack(inp.v).astype(np.float64)
+    r = torch.zeros(M, device="cuda")
+    total, t = tau * rounds, 0
+    widths, etas = [], []
+    for k in range(rounds):
+        for s in range(tau):
+            eta = f32(0.5 * lr0 * (1.0 + np.cos(np.pi * t / total)))
+            gk = inp.grads(t); t += 1
+            if s < tau - 1:
+                plan.local_sgd_step(x, v, _rows(inp, gk), eta, mu, wd)
+                xo, vo = O.local_sgd_step(xo, vo, np.stack(gk), eta, mu, wd)
+            else:
+                plan.round(x, v, _rows(inp, gk), eta, mu, wd, pull, push, r_out=r)
+                xo, vo, ro, _, _ = O.dppf_round(xo, vo, np.stack(gk), eta, mu, wd, pull, push)
+                assert_rel(r.cpu().numpy(), ro, 1e-4, f"r in round {k}")
+        final = torch.zeros(M, device="cuda")
+        plan.dist_norms(x, final)
+        widths.append(final.cpu().numpy().astype(np.float64))
+        etas.append(eta)
+    assert_params_close(download_rows(x), xo, inp.offsets, tau * rounds, "x after all rounds")
+    target = push / pull
+    mean_width = np.array([w.mean() for w in widths])
+    # while eta is large the noise term is visible ...
+    assert mean_width[rounds // 5] > 1.2 * target, mean_width[rounds // 5]
+    # ... and the excess over lambda/alpha shrinks with eta: within a fixed multiple of eta*sigma0 (plus 1 %)
+    late = range(rounds // 2, rounds)
+    for k in late:
+        assert abs(mean_width[k] - target) <= 12.0 * etas[k] * sigma0 + 0.01 * target, (k, mean_width[k], etas[k])
+    assert abs(mean_width[-1] - target) < 0.01 * target, mean_width[-1]
+    assert np.all(np.abs(widths[-1] - target) < 0.05 * target), widths[-1]
+    plan.close()
+
+
 @pytest.mark.parametrize("schedule", ["fixed", "increasing"])
 def test_alg1_loop_matches_the_oracle(schedule):
     # Alg. 1 end to end through the loop helper: tau-step periods, scheduled push, final average
