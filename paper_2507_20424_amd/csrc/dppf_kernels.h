@@ -46,6 +46,14 @@ constexpr int sweep_tile_elems(int M) {
   return M < kSmallTileFromM ? 4096 : (M <= kMaxTemplM ? 2048 : (M <= kMaxLdsM ? kLdsTileElems : kStepTileElems));
 }
 constexpr int vectors_per_lane(int tile_elems) { return tile_elems / (4 * kBlock); }
+// Workers whose loads the fused sweeps 1 keep in flight ahead of the worker they work on (`arrays`
+// = streams per worker: x, v, g or x, m1, m2, g).  With two vectors per lane and worker (5 workers
+// and more) a single worker's requests are too few to cover the latency, and as many workers as 48
+// vectors per lane allow are requested ahead (M = 8: sweep 1 of the fused round -4 %); with four
+// vectors per worker the look-ahead gains nothing (M = 4: +1 %) and is left out.
+constexpr int lookahead(int M, int U, int arrays) {
+  return U >= 4 ? 0 : (48 / (arrays * U) - 1 > M ? M : 48 / (arrays * U) - 1);
+}
 
 // Resident blocks per CU by traffic pattern (measured): kernels that mix reads and writes run
 // fastest with ONE block per CU -- fewer concurrently open DRAM rows and longer same-direction
@@ -374,20 +382,30 @@ __device__ __forceinline__ void sweep1_tile(const Tile tl, int T, float* const* 
     }
     f4 xv[U][M];
     if (SGD) {
-#pragma unroll
-      for (int m = 0; m < M; ++m) {
-        f4 vv[U], gv[U];
+      // The loads of the next kAhead workers are issued before worker m's data are waited for, so a
+      // wave has several workers' worth of requests in flight; written as one worker after the
+      // other, each wave drains its loads before it issues the stores and the next worker's loads
+      // (the compiler cannot move loads above stores of possibly overlapping memory).
+      constexpr int kAhead = lookahead(M, U, 3);
+      f4 vv[M][U], gv[M][U];
+      auto request = [&](int m) {
 #pragma unroll
         for (int k = 0; k < U; ++k) {
           xv[k][m] = KEEPX ? load4<FULL>(x[m] + e[k], n[k]) : load4_stream<FULL>(x[m] + e[k], n[k]);
-          vv[k] = load4_stream<FULL>(v[m] + e[k], n[k]);
-          gv[k] = load4_stream<FULL>(g[m] + e[k], n[k]);
+          vv[m][k] = load4_stream<FULL>(v[m] + e[k], n[k]);
+          gv[m][k] = load4_stream<FULL>(g[m] + e[k], n[k]);
         }
+      };
+#pragma unroll
+      for (int m = 0; m < kAhead && m < M; ++m) request(m);
+#pragma unroll
+      for (int m = 0; m < M; ++m) {
+        if (m + kAhead < M) request(m + kAhead);
 #pragma unroll
         for (int k = 0; k < U; ++k) {
           // Alg. 1 local step with heavy-ball momentum: g' = g + wd x; v <- mu v + g'; x <- x - lr v
-          const f4 ge = fma4(xv[k][m], wd, gv[k]);
-          const f4 vn = fma4(vv[k], mu, ge);
+          const f4 ge = fma4(xv[k][m], wd, gv[m][k]);
+          const f4 vn = fma4(vv[m][k], mu, ge);
           store4_stream<FULL>(v[m] + e[k], vn, n[k]);
           // The stepped x is not written: sweep 2 re-derives it from the old x and the new v with
           // the same fused multiply-add (same bits), which trades 4 written bytes for 4 read bytes
@@ -914,26 +932,33 @@ __device__ __forceinline__ void adamw_reduce_tile(const Tile tl, int T, float* c
       e[k] = 4 * (threadIdx.x + (it * U + k) * kBlock);
       n[k] = FULL ? 4 : tl.count - e[k];
     }
-    // worker by worker (see sweep1_tile): here 7 % faster than all workers' loads at once
+    // worker by worker (see sweep1_tile: 7 % faster here than all workers' loads at once), the next
+    // workers' loads requested ahead
+    constexpr int kAhead = lookahead(M, U, 4);
+    f4 av[M][U], sv[M][U], gv[M][U];
+    auto request = [&](int m) {
+      const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
+#pragma unroll
+      for (int k = 0; k < U; ++k) {
+        xv[k][m] = load4_stream<FULL>(xp[slot] + tl.offset + e[k], n[k]);
+        av[m][k] = load4_stream<FULL>(ap[slot] + tl.offset + e[k], n[k]);
+        sv[m][k] = load4_stream<FULL>(sp[slot] + tl.offset + e[k], n[k]);
+        gv[m][k] = load4_stream<FULL>(gp[slot] + tl.offset + e[k], n[k]);
+      }
+    };
+#pragma unroll
+    for (int m = 0; m < kAhead && m < M; ++m) request(m);
 #pragma unroll
     for (int m = 0; m < M; ++m) {
+      if (m + kAhead < M) request(m + kAhead);
       const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
       float* x = xp[slot] + tl.offset;
       float* a = ap[slot] + tl.offset;
       float* q = sp[slot] + tl.offset;
-      const float* g = gp[slot] + tl.offset;
-      f4 av[U], sv[U], gv[U];
-#pragma unroll
-      for (int k = 0; k < U; ++k) {
-        xv[k][m] = load4_stream<FULL>(x + e[k], n[k]);
-        av[k] = load4_stream<FULL>(a + e[k], n[k]);
-        sv[k] = load4_stream<FULL>(q + e[k], n[k]);
-        gv[k] = load4_stream<FULL>(g + e[k], n[k]);
-      }
 #pragma unroll
       for (int k = 0; k < U; ++k) {
         f4 xn, an, sn;
-        adamw_vec(xv[k][m], av[k], sv[k], gv[k], hp, xn, an, sn);
+        adamw_vec(xv[k][m], av[m][k], sv[m][k], gv[m][k], hp, xn, an, sn);
         store4_stream<FULL>(a + e[k], an, n[k]);
         store4_stream<FULL>(q + e[k], sn, n[k]);
         store4<FULL>(x + e[k], xn, n[k]);     // read again by sweep 2
