@@ -33,6 +33,21 @@ int dppf_util_copy(float* dst, const float* src, int64_t n, void* stream);
 int dppf_util_stream_probe(float* base, int64_t stride, int64_t n, int reads, int writes, int inplace,
                            int blocks_per_cu, int on_demand, void* stream);
 
+/* Measurement aid: the same kind of traffic in the order the library's sweeps produce it.  The
+ * arrays (array k at base + k*stride floats, as above) form `groups` groups of `reads_per_group`
+ * arrays each.  Inside a tile of 256*vectors 16-byte vectors a lane takes one group after the
+ * other: it loads the group's reads_per_group*vectors vectors, adds them and overwrites the group's
+ * first array with the sum (with half the value when reads_per_group is 1) -- per group and
+ * element reads_per_group reads and one write in place, the pattern of a sweep that handles one
+ * worker after the other.  `ahead` = how many groups' loads are requested before the current
+ * group's data are waited for.  One tile per work item; on_demand and blocks_per_cu as above (same
+ * per-device counter, same rule about overlapping calls); only elements below the largest multiple
+ * of the tile are touched.  Supported (groups, reads_per_group, vectors, ahead): (2,3,4,0) (4,3,4,0)
+ * (4,3,4,3) (4,3,2,0) (4,3,8,0) (4,2,4,0) (4,2,4,3) (4,2,8,0) (8,3,2,0) (8,3,2,7) (8,2,2,0) (8,2,2,7)
+ * (16,3,2,0) (16,3,2,7) (16,2,2,7) (4,1,4,0); anything else returns DPPF_EINVAL.  */
+int dppf_util_stream_probe_grouped(float* base, int64_t stride, int64_t n, int groups, int reads_per_group,
+                                   int vectors, int ahead, int blocks_per_cu, int on_demand, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -812,6 +812,15 @@ int dppf_util_stream_probe(float* base, int64_t stride, int64_t n, int reads, in
                              static_cast<hipStream_t>(stream));
 }
 
+int dppf_util_stream_probe_grouped(float* base, int64_t stride, int64_t n, int groups, int reads_per_group,
+                                   int vectors, int ahead, int blocks_per_cu, int on_demand, void* stream) {
+  if (!base || n < 0 || stride < n || blocks_per_cu < 1 || blocks_per_cu > 16) return DPPF_EINVAL;
+  if (reinterpret_cast<uintptr_t>(base) & 15u || (stride & 3)) return DPPF_EINVAL;
+  if (n / 1024 >= INT32_MAX) return DPPF_ELIMIT;
+  return launch_stream_probe_grouped(base, stride, n, groups, reads_per_group, vectors, ahead, blocks_per_cu,
+                                     on_demand, static_cast<hipStream_t>(stream));
+}
+
 // ---- timing
 int dppf_plan_timing_enable(dppf_plan* p, int enable) {
   if (!p) return DPPF_EINVAL;

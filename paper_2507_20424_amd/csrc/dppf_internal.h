@@ -238,6 +238,8 @@ int launch_flat_setup(Tile* tiles, long long d, int tile_elems, int ntiles, int 
 int launch_copy(float* dst, const float* src, int64_t n, hipStream_t s);
 int launch_stream_probe(float* base, int64_t stride, int64_t n, int reads, int writes, int inplace,
                         int blocks_per_cu, int on_demand, hipStream_t s);
+int launch_stream_probe_grouped(float* base, int64_t stride, int64_t n, int groups, int reads_per_group,
+                                int vectors, int ahead, int blocks_per_cu, int on_demand, hipStream_t s);
 // dppf_launch_any.hip -- any M, stored average
 int launch_mean_any(dppf_plan* p, const void** xp, const void** xbarp, hipStream_t s);
 int launch_norms_any(dppf_plan* p, const void** xp, const void** xbarp, GridShape* shape, hipStream_t s);

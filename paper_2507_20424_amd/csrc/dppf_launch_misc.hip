@@ -118,6 +118,48 @@ __global__ __launch_bounds__(kBlock) void k_probe(float* __restrict__ base, long
   if (W == 0 && acc.x + acc.y + acc.z + acc.w == 123.456f) sink[0] = acc.x;   // keeps the loads alive
 }
 
+
+// ------------------------------------ the same traffic in the order the sweeps use
+// NG groups of GR streams each (group j: streams j*GR .. j*GR+GR-1), taken one group after the
+// other inside a tile of kBlock*U vectors, the way the fused sweeps take one worker after the
+// other: a lane loads the group's GR*U vectors, adds them and overwrites the group's first stream
+// with the sum (half the value when the group is a single stream): GR reads and 1 write in place
+// per group and element, with the loads of the next AHEAD groups requested before the current
+// group's are waited for.  One tile per work item, handed out like the sweeps' tiles.  The memory
+// traffic of a sweep with none of its arithmetic, reductions or pointer tables.
+template <int NG, int GR, int U, int AHEAD>
+__global__ __launch_bounds__(kBlock) void k_probe_grouped(float* __restrict__ base, long long stride, const Walk wk) {
+  constexpr long long kTile = static_cast<long long>(kBlock) * U * 4;
+  walk<false>(
+      wk, 1,
+      [&](int item) {
+        float* at = base + item * kTile + 4 * threadIdx.x;
+        f4 buf[NG][GR][U];
+        auto request = [&](int j) {
+#pragma unroll
+          for (int r = 0; r < GR; ++r)
+#pragma unroll
+            for (int k = 0; k < U; ++k)
+              buf[j][r][k] = load4_stream<true>(at + (j * GR + r) * stride + 4 * k * kBlock, 4);
+        };
+#pragma unroll
+        for (int j = 0; j < AHEAD && j < NG; ++j) request(j);
+#pragma unroll
+        for (int j = 0; j < NG; ++j) {
+          if (j + AHEAD < NG) request(j + AHEAD);
+#pragma unroll
+          for (int k = 0; k < U; ++k) {
+            f4 sum = buf[j][0][k];
+#pragma unroll
+            for (int r = 1; r < GR; ++r) sum += buf[j][r][k];
+            if (GR == 1) sum = sum * 0.5f;   // storing back the very value loaded would be dropped as a dead store
+            store4_stream<true>(at + (j * GR) * stride + 4 * k * kBlock, sum, 4);
+          }
+        }
+      },
+      [](int) {}, [](int) {});
+}
+
 }  // namespace
 
 int launch_copy(float* dst, const float* src, int64_t n, hipStream_t s) {
@@ -176,6 +218,49 @@ int launch_stream_probe(float* base, int64_t stride, int64_t n, int reads, int w
   DPPF_PROBE(24, 8, 1, true)
 #undef DPPF_PROBE
   return DPPF_EINVAL;   // this read/write mix is not instantiated
+}
+
+int launch_stream_probe_grouped(float* base, int64_t stride, int64_t n, int groups, int reads_per_group,
+                                int vectors, int ahead, int blocks_per_cu, int on_demand, hipStream_t s) {
+  int dev = 0, cus = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  Sched* sched = nullptr;
+  HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&sched), HIP_SYMBOL(g_probe_sched)));
+  const dim3 block(kBlock);
+#define DPPF_PROBE_G(NG_, GR_, U_, A_)                                                                        \
+  if (groups == NG_ && reads_per_group == GR_ && vectors == U_ && ahead == A_) {                              \
+    const long long tiles_ = n / (static_cast<long long>(kBlock) * U_ * 4);                                   \
+    if (tiles_ < 1 || tiles_ > INT32_MAX) return DPPF_EINVAL;                                                 \
+    long long grid_ = static_cast<long long>(cus) * blocks_per_cu;                                            \
+    if (grid_ > tiles_) grid_ = tiles_;                                                                       \
+    const Walk walk_ = dppf_walk::make_walk(static_cast<int>(tiles_), static_cast<int>(tiles_), kBlock * U_ * 4, \
+                                            static_cast<int>(grid_), 1, 1,                                    \
+                                            on_demand ? dppf_walk::kOnDemand : dppf_walk::kEvenSplit,         \
+                                            4.0 * NG_ * (GR_ + 1), sched);                                    \
+    hipLaunchKernelGGL((k_probe_grouped<NG_, GR_, U_, A_>), dim3(static_cast<unsigned>(grid_)), block, 0, s,  \
+                       base, static_cast<long long>(stride), walk_);                                          \
+    HIP_TRY(hipGetLastError());                                                                               \
+    return DPPF_OK;                                                                                           \
+  }
+  DPPF_PROBE_G(2, 3, 4, 0)    // two workers
+  DPPF_PROBE_G(4, 3, 4, 0)    // sweep 1 of the fused round, 4 workers
+  DPPF_PROBE_G(4, 3, 4, 3)
+  DPPF_PROBE_G(4, 3, 2, 0)
+  DPPF_PROBE_G(4, 3, 8, 0)
+  DPPF_PROBE_G(4, 2, 4, 0)    // sweep 2 of the fused round, 4 workers
+  DPPF_PROBE_G(4, 2, 4, 3)
+  DPPF_PROBE_G(4, 2, 8, 0)
+  DPPF_PROBE_G(8, 3, 2, 0)    // 8 workers
+  DPPF_PROBE_G(8, 3, 2, 7)
+  DPPF_PROBE_G(8, 2, 2, 0)
+  DPPF_PROBE_G(8, 2, 2, 7)
+  DPPF_PROBE_G(16, 3, 2, 0)   // 16 workers
+  DPPF_PROBE_G(16, 3, 2, 7)
+  DPPF_PROBE_G(16, 2, 2, 7)
+  DPPF_PROBE_G(4, 1, 4, 0)    // the plain round's sweep 2 (read x, write x)
+#undef DPPF_PROBE_G
+  return DPPF_EINVAL;   // this shape is not instantiated
 }
 
 }  // namespace dppf_detail

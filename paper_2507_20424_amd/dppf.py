@@ -67,6 +67,8 @@ def load():
         "dppf_util_copy": (ctypes.c_int, [vp, vp, i64, vp]),
         "dppf_util_stream_probe": (ctypes.c_int, [vp, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                   ctypes.c_int, ctypes.c_int, vp]),
+        "dppf_util_stream_probe_grouped": (ctypes.c_int, [vp, i64, i64, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                                          ctypes.c_int, ctypes.c_int, ctypes.c_int, vp]),
         "dppf_plan_timing_enable": (ctypes.c_int, [vp, ctypes.c_int]),
         "dppf_plan_timing_read": (ctypes.c_int, [vp, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(f), ctypes.c_int]),
     }
@@ -292,9 +294,17 @@ def push_schedule(kind: str, push: float, t: int, t_total: int) -> float:
 
 def util_stream_probe(base, stride: int, n: int, reads: int, writes: int, inplace: bool, blocks_per_cu: int,
                       on_demand: bool = False, stream=None) -> None:
-    """Launch the library's streaming probe (measurement aid, see include/dppf.h)."""
+    """Launch the library's streaming probe (measurement aid, see include/dppf_util.h)."""
     _check(load().dppf_util_stream_probe(_dev(base), stride, n, reads, writes, 1 if inplace else 0, blocks_per_cu,
                                          1 if on_demand else 0, _stream(stream)), "dppf_util_stream_probe")
+
+
+def util_stream_probe_grouped(base, stride: int, n: int, groups: int, reads_per_group: int, vectors: int,
+                              ahead: int, blocks_per_cu: int, on_demand: bool = False, stream=None) -> None:
+    """Launch the streaming probe that takes its arrays group by group (see include/dppf_util.h)."""
+    _check(load().dppf_util_stream_probe_grouped(_dev(base), stride, n, groups, reads_per_group, vectors, ahead,
+                                                 blocks_per_cu, 1 if on_demand else 0, _stream(stream)),
+           "dppf_util_stream_probe_grouped")
 
 
 def sweep_tile_elems(M: int) -> int:

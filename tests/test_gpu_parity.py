@@ -529,6 +529,34 @@ def test_measurement_utilities():
         assert torch.equal(big[length:2 * length], big[:length]) and torch.all(big[2 * length:] == 0)
 
 
+def test_grouped_stream_probe_sums_each_group_into_its_first_array():
+    lib = dppf.load()
+    import ctypes
+    groups, per_group, vectors, ahead = 8, 3, 2, 7
+    tile = 256 * vectors * 4
+    length = tile * 1500 + 100                       # the tail past the last whole tile stays untouched
+    stride = length + 64
+    for on_demand in (False, True):
+        buf = torch.zeros(groups * per_group * stride, device="cuda")
+        for k in range(groups * per_group):
+            buf[k * stride:k * stride + length] = float(k + 1)
+        before = buf.clone()
+        dppf.util_stream_probe_grouped(buf, stride, length, groups, per_group, vectors, ahead, 1, on_demand)
+        whole = tile * 1500
+        for j in range(groups):
+            first = j * per_group
+            want = float(sum(first + r + 1 for r in range(per_group)))
+            got = buf[first * stride:first * stride + stride]
+            assert torch.all(got[:whole] == want)
+            assert torch.equal(got[whole:], before[first * stride + whole:(first + 1) * stride])
+            for r in range(1, per_group):
+                k = first + r
+                assert torch.equal(buf[k * stride:(k + 1) * stride], before[k * stride:(k + 1) * stride])
+    buf = torch.zeros(12 * stride, device="cuda")
+    assert lib.dppf_util_stream_probe_grouped(ctypes.c_void_p(buf.data_ptr()), stride, length, 5, 3, 4, 0, 1, 0,
+                                              None) == -1
+
+
 @pytest.mark.parametrize("M", [12, 17, 35])
 def test_many_workers_on_a_list_that_fills_the_chip(M):
     # M > 16 goes through a stored average and groups of up to 16 workers; here with more tiles than
