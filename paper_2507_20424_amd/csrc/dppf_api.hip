@@ -53,22 +53,24 @@ constexpr size_t kRaiseLdsLimitFrom = 32 * 1024;
 constexpr size_t kLdsLimitBytes =
     static_cast<size_t>(kMaxLdsM) * kBlock * sizeof(f4) + sizeof(double) * kWaves * (kMaxLdsM + 1);
 
-int blocks_per_cu(int device, const void* kernel, size_t dynamic_lds, int* per_cu_out) {
+int blocks_per_cu(int device, const void* kernel, int block_threads, size_t dynamic_lds, int* per_cu_out) {
   if (device < 0 || device >= kMaxDevices) return DPPF_ELIMIT;
   std::lock_guard<std::mutex> lock(g_device_mutex);
   DeviceState& dev = g_device[device];
   for (int i = 0; i < dev.nocc; ++i)
-    if (dev.occ_kernel[i] == kernel) {
+    if (dev.occ_kernel[i] == kernel && dev.occ_threads[i] == block_threads && dev.occ_lds[i] == dynamic_lds) {
       *per_cu_out = dev.occ_per_cu[i];
       return DPPF_OK;
     }
   if (dynamic_lds >= kRaiseLdsLimitFrom)
     HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kLdsLimitBytes)));
   int per_cu = 0;
-  HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kBlock, dynamic_lds));
+  HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, block_threads, dynamic_lds));
   if (per_cu < 1) per_cu = 1;
   if (dev.nocc < kOccupancySlots) {      // a full table only means the query is repeated
     dev.occ_kernel[dev.nocc] = kernel;
+    dev.occ_threads[dev.nocc] = block_threads;
+    dev.occ_lds[dev.nocc] = dynamic_lds;
     dev.occ_per_cu[dev.nocc] = per_cu;
     ++dev.nocc;
   }

@@ -59,7 +59,9 @@ constexpr int kOccupancySlots = 1024;
 struct DeviceState {
   int num_cu = 0;
   int nocc = 0;
-  const void* occ_kernel[kOccupancySlots];
+  const void* occ_kernel[kOccupancySlots];   // key: kernel, block size, dynamic LDS bytes
+  int occ_threads[kOccupancySlots];
+  size_t occ_lds[kOccupancySlots];
   int occ_per_cu[kOccupancySlots];
   unsigned char* static_scratch = nullptr;
 };
@@ -114,14 +116,15 @@ struct GridShape {
 };
 
 // Resident blocks per CU of a kernel on the plan's device (queried once per device and kernel).
-int blocks_per_cu(int device, const void* kernel, size_t dynamic_lds, int* per_cu);
+int blocks_per_cu(int device, const void* kernel, int block_threads, size_t dynamic_lds, int* per_cu);
 
 // ---- grid sizes: enough resident blocks to fill every CU, never more blocks than items
 template <typename K>
 int grid_for(dppf_plan* p, const TileList& list, K kernel, int per_tile_items, int tiles_per_item, int want_per_cu,
-             size_t dynamic_lds, int* gfull_out, int* grid_out) {
+             size_t dynamic_lds, int* gfull_out, int* grid_out, int block_threads = kBlock) {
   int per_cu = 0;
-  const int rc = blocks_per_cu(p->device, reinterpret_cast<const void*>(kernel), dynamic_lds, &per_cu);
+  const int rc =
+      blocks_per_cu(p->device, reinterpret_cast<const void*>(kernel), block_threads, dynamic_lds, &per_cu);
   if (rc) return rc;
   if (per_cu > want_per_cu) per_cu = want_per_cu;
   if (per_cu > kMaxBlocksPerCU - 1) per_cu = kMaxBlocksPerCU - 1;

@@ -182,7 +182,7 @@ inline int build_tile_list(int T, const int64_t* numel, int tile_elems, std::vec
 enum OnDemand { kEvenSplit, kOnDemand, kOnDemandReducing };
 constexpr int kMinRoundsOnDemand = 4;
 constexpr int kMinRoundsAllOnDemandReducing = 32;     // per-tile sums: only worth it on long lists
-constexpr double kAllOnDemandBytes = 2.2e9;           // about 0.4 ms of traffic
+constexpr double kAllOnDemandBytes = 1.5e9;           // about 0.25 ms of traffic
 
 // Items [0, returned value) of `count` are split evenly over `blocks` blocks, the rest handed out
 // on demand; returns count when nothing is.  bytes_per_item: what one item moves.

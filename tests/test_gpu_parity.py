@@ -559,8 +559,9 @@ def test_grouped_stream_probe_sums_each_group_into_its_first_array():
 
 @pytest.mark.parametrize("M", [12, 17, 35])
 def test_many_workers_on_a_list_that_fills_the_chip(M):
-    # M > 16 goes through a stored average and groups of up to 16 workers; here with more tiles than
-    # compute units, so the groups' launches must share one layout of the partial sums
+    # M = 12: register-resident sweeps on 2048-element tiles; M = 17, 35: every worker's vector staged
+    # in LDS (1024-element tiles); here with more tiles than compute units, so part of the tiles is
+    # handed out on demand and the partial sums have one row per such tile
     spec = W.small_spec(M=M, seed=900 + M, shapes=((1_300_000,), (777,), (1_200_003,), (5,)))
     h = _hyper(spec)
     inp = W.make_inputs(spec)

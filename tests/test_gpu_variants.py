@@ -212,8 +212,8 @@ LONG_SHAPES = ((2_500_000,), (1_234_567,), (1_000_003,), (777,))
 def test_every_entry_point_on_a_list_with_an_on_demand_tail(M):
     # With four or more tiles per thread block the read-write sweeps hand the tail of their tiles
     # out on demand; every entry point must give the oracle's result through that path too
-    # (M = 12: half a tile per pass, registers beyond the first 256; M = 17: the staged kernels for
-    # more workers than fit in registers).
+    # (M = 12: two vectors per lane and worker, registers beyond the first 256; M = 17: the kernels
+    # that stage the workers in LDS; M = 40: the kernels that store the average).
     spec = W.small_spec(M=M, seed=950 + M, shapes=LONG_SHAPES)
     _, nfull, _ = dppf.layout_tiles(spec.numel)      # the largest tiles any kernel uses
     assert nfull >= 4 * torch.cuda.get_device_properties(0).multi_processor_count
