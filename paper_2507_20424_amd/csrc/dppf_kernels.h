@@ -104,6 +104,19 @@ typedef __attribute__((address_space(1))) f4u* gvec_out;
 typedef __attribute__((address_space(1))) const float* gf_in;
 typedef __attribute__((address_space(1))) float* gf_out;
 
+// Entry `slot` of a pointer table (slot the same for every lane), fetched through the scalar path.
+// The tables are written before the launch and never during it, but a kernel that also stores
+// through the pointers it fetched gives the compiler no way to know that; left to itself it fetches
+// entries inside a loop over the workers with vector loads, and those share the in-order counter
+// of the data loads: waiting for the next workers' pointers then means waiting for every data load
+// issued before them, and the overlap between one group of workers and the next is gone.
+template <typename P>
+__device__ __forceinline__ P* table_entry(P* const* table, size_t slot) {
+  typedef P* entry;
+  typedef __attribute__((address_space(4))) const entry* constant_table;   // the ENTRIES sit in constant memory
+  return ((constant_table)(table))[slot];
+}
+
 template <bool FULL>
 __device__ __forceinline__ f4 load4(const float* p, int n) {
   if (FULL || n >= 4) return *(gvec_in)(p);
@@ -1096,7 +1109,7 @@ __device__ __forceinline__ void mean_any_tile(const Tile tl, int M, int T,
 #pragma unroll
     for (int k = 0; k < kAnyChunk; ++k)
       if (m + k < M) {
-        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+        const float* base = table_entry(xp, static_cast<size_t>(m + k) * T + tl.tensor) + tl.offset;
 #pragma unroll
         for (int it = 0; it < kAnyVec; ++it) {
           const int e = 4 * (threadIdx.x + it * kBlock);
@@ -1154,7 +1167,7 @@ __device__ __forceinline__ void norms_any_tile(const Tile tl, int M, int T, floa
 #pragma unroll
     for (int k = 0; k < kAnyChunk; ++k)
       if (m + k < M) {
-        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+        const float* base = table_entry(xp, static_cast<size_t>(m + k) * T + tl.tensor) + tl.offset;
 #pragma unroll
         for (int it = 0; it < kAnyVec; ++it) {
           const int e = 4 * (threadIdx.x + it * kBlock);
@@ -1214,7 +1227,7 @@ __device__ __forceinline__ void update_any_tile(const Tile tl, int M, int T, flo
 #pragma unroll
     for (int k = 0; k < kAnyChunk; ++k)
       if (m + k < M) {
-        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+        const float* base = table_entry(xp, static_cast<size_t>(m + k) * T + tl.tensor) + tl.offset;
 #pragma unroll
         for (int it = 0; it < kAnyVec; ++it) {
           const int e = 4 * (threadIdx.x + it * kBlock);
@@ -1224,7 +1237,7 @@ __device__ __forceinline__ void update_any_tile(const Tile tl, int M, int T, flo
 #pragma unroll
     for (int k = 0; k < kAnyChunk; ++k)
       if (m + k < M) {
-        float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+        float* base = table_entry(xp, static_cast<size_t>(m + k) * T + tl.tensor) + tl.offset;
         const float c = coef[m + k].c;
         const bool stay = !EXACT && coef[m + k].skip != 0;
 #pragma unroll
@@ -1278,7 +1291,7 @@ __device__ __forceinline__ void unit_sum_tile(const Tile tl, int M, int T, float
 #pragma unroll
     for (int k = 0; k < kAnyChunk; ++k)
       if (m + k < M) {
-        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+        const float* base = table_entry(xp, static_cast<size_t>(m + k) * T + tl.tensor) + tl.offset;
         wgt[k] = coef[m + k].inv_r;
 #pragma unroll
         for (int it = 0; it < kAnyVec; ++it) {
@@ -1338,7 +1351,7 @@ __device__ __forceinline__ void seq_any_tile(const Tile tl, int M, int T, float*
 #pragma unroll
     for (int k = 0; k < kAnyChunk; ++k)
       if (m + k < M) {
-        const float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+        const float* base = table_entry(xp, static_cast<size_t>(m + k) * T + tl.tensor) + tl.offset;
 #pragma unroll
         for (int it = 0; it < kAnyVec; ++it) {
           const int e = 4 * (threadIdx.x + it * kBlock);
@@ -1351,7 +1364,7 @@ __device__ __forceinline__ void seq_any_tile(const Tile tl, int M, int T, float*
     for (int k = 0; k < kAnyChunk; ++k) {
       p[k] = 0.f;
       if (m + k < M) {
-        float* base = xp[static_cast<size_t>(m + k) * T + tl.tensor] + tl.offset;
+        float* base = table_entry(xp, static_cast<size_t>(m + k) * T + tl.tensor) + tl.offset;
         const float scale = WRITE ? (coef[m + k].skip != 0 ? 0.f : -coef[m + k].c) : 0.f;
 #pragma unroll
         for (int it = 0; it < kAnyVec; ++it) {
@@ -1420,12 +1433,12 @@ struct LdsChunk {
     for (int k = 0; k < kLdsChunk; ++k) {
       const int m = m0 + k < M ? m0 + k : M - 1;
       const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
-      x[k] = load4_stream<FULL>(xp[slot] + tl.offset + e, n);
+      x[k] = load4_stream<FULL>(table_entry(xp, slot) + tl.offset + e, n);
       if (OPT != 0) {
-        a[k] = load4_stream<FULL>(o.vp[slot] + tl.offset + e, n);
-        g[k] = load4_stream<FULL>(o.gp[slot] + tl.offset + e, n);
+        a[k] = load4_stream<FULL>(table_entry(o.vp, slot) + tl.offset + e, n);
+        g[k] = load4_stream<FULL>(table_entry(o.gp, slot) + tl.offset + e, n);
       }
-      if (OPT == 2) s[k] = load4_stream<FULL>(o.sp[slot] + tl.offset + e, n);
+      if (OPT == 2) s[k] = load4_stream<FULL>(table_entry(o.sp, slot) + tl.offset + e, n);
     }
   }
   __device__ __forceinline__ f4 stepped(int k, int m, int T, const Tile& tl, int e, int n, float* const* xp,
@@ -1435,14 +1448,14 @@ struct LdsChunk {
     if (OPT == 1) {
       const f4 ge = fma4(x[k], o.wd, g[k]);
       const f4 vn = fma4(a[k], o.mu, ge);
-      store4_stream<FULL>(o.vp[slot] + tl.offset + e, vn, n);
+      store4_stream<FULL>(table_entry(o.vp, slot) + tl.offset + e, vn, n);
       return fma4(vn, -o.lr, x[k]);
     }
     f4 xn, an, sn;
     adamw_vec(x[k], a[k], s[k], g[k], o.adam, xn, an, sn);
-    store4_stream<FULL>(o.vp[slot] + tl.offset + e, an, n);
-    store4_stream<FULL>(o.sp[slot] + tl.offset + e, sn, n);
-    store4<FULL>(xp[slot] + tl.offset + e, xn, n);
+    store4_stream<FULL>(table_entry(o.vp, slot) + tl.offset + e, an, n);
+    store4_stream<FULL>(table_entry(o.sp, slot) + tl.offset + e, sn, n);
+    store4<FULL>(table_entry(xp, slot) + tl.offset + e, xn, n);
     return first_components<FULL>(xn, n);
   }
 };
@@ -1528,8 +1541,8 @@ __device__ __forceinline__ void sweep2_lds_tile(const Tile tl, int M, int T, flo
     for (int k = 0; k < kLdsChunk; ++k) {
       const int m = m0 + k < M ? m0 + k : M - 1;
       const size_t slot = static_cast<size_t>(m) * T + tl.tensor;
-      cx[k] = load4_stream<FULL>(xp[slot] + tl.offset + e, n);
-      if (MODE == 1) cv[k] = load4_stream<FULL>(vp[slot] + tl.offset + e, n);
+      cx[k] = load4_stream<FULL>(table_entry(xp, slot) + tl.offset + e, n);
+      if (MODE == 1) cv[k] = load4_stream<FULL>(table_entry(vp, slot) + tl.offset + e, n);
     }
   };
   auto consume = [&](f4 (&cx)[kLdsChunk], f4 (&cv)[kLdsChunk], int m0) {
@@ -1571,7 +1584,7 @@ __device__ __forceinline__ void sweep2_lds_tile(const Tile tl, int M, int T, flo
     f4 moved = fma4(mo - (xm - x0), coef[m].c, xm);
     if (MODE == 2) moved = fma4(usum, k2, moved);
     const bool stay = MODE != 2 && coef[m].skip != 0;
-    store4_stream<FULL>(xp[static_cast<size_t>(m) * T + tl.tensor] + tl.offset + e, stay ? xm : moved, n);
+    store4_stream<FULL>(table_entry(xp, static_cast<size_t>(m) * T + tl.tensor) + tl.offset + e, stay ? xm : moved, n);
   }
 }
 

@@ -37,15 +37,14 @@ int launch_sweep1_lds(dppf_plan* p, const void** xp, int opt, const LdsOptArgs& 
   const double bytes = (opt == 0 ? 4.0 : (opt == 1 ? 16.0 : 28.0)) * p->M;
   // a pure read keeps the even split (per-tile sums would cost more than they win), see make_walk's policy
   const OnDemand policy = opt == 0 && !store_avg ? dppf_walk::kEvenSplit : dppf_walk::kOnDemandReducing;
-  // Sweep 1 leaves the memory system idle while a block reads its staged vectors back and while the
-  // first loads of its next tile are on their way: a second resident block fills those gaps where
-  // the LDS holds two blocks' stages (up to 19 workers; M = 17: fused sweep 1 -11 %, pure-read
-  // sweep 1 -38 %).  Smaller blocks that would fit twice for any M were slower than one block of
-  // 256 (128 threads x 2: +10 %): each start of the load pipeline costs a memory latency, and they
-  // start it twice per tile.  Sweep 2 writes what it reads and is fastest from one block per CU.
-  constexpr int kSweep1BlocksPerCU = 2;
+  // Like the register-resident sweeps: a sweep that only reads streams best from two resident
+  // blocks per CU (M = 17: -38 %; the LDS holds two stages up to 19 workers), one that also writes
+  // from one.  Smaller blocks that would fit twice for any M were slower than one block of 256
+  // threads (128 threads x 2: +10 %): each start of the load pipeline costs a memory latency, and
+  // they start it twice per tile.
+  const int want_per_cu = opt == 0 && !store_avg ? kBlocksPerCUReadOnly : kBlocksPerCUReadWrite;
 #define DPPF_LDS1(OPT_, XBAR_) \
-  return launch_on(p, k_sweep1_lds<OPT_, XBAR_>, kSweep1BlocksPerCU, lds, policy, bytes, shape, s, x, o, xb, parts, ps)
+  return launch_on(p, k_sweep1_lds<OPT_, XBAR_>, want_per_cu, lds, policy, bytes, shape, s, x, o, xb, parts, ps)
   if (store_avg) {
     if (opt == 0) DPPF_LDS1(0, 1);
     if (opt == 1) DPPF_LDS1(1, 1);
@@ -66,7 +65,7 @@ int launch_sweep2_lds(dppf_plan* p, const void** xp, const void** vp, int mode, 
   const float* const* v = (const float* const*)(vp);
   const double bytes = (mode == 1 ? 12.0 : 8.0) * p->M;
 #define DPPF_LDS2(MODE_) \
-  return launch_on(p, k_sweep2_lds<MODE_>, 1, lds, dppf_walk::kOnDemand, bytes, nullptr, s, x, v, lr, p->coef, k2)
+  return launch_on(p, k_sweep2_lds<MODE_>, kBlocksPerCUReadWrite, lds, dppf_walk::kOnDemand, bytes, nullptr, s, x, v, lr, p->coef, k2)
   if (mode == 0) DPPF_LDS2(0);
   if (mode == 1) DPPF_LDS2(1);
   if (mode == 2) DPPF_LDS2(2);

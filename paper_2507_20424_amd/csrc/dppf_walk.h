@@ -178,19 +178,24 @@ inline int build_tile_list(int T, const int64_t* numel, int tile_elems, std::vec
 //    in the reducing sweeps), long ones gain more than that from the compact window.
 // So: launches that move more than kAllOnDemandBytes hand out everything, shorter ones the second
 // half; the pure-read reducing sweeps (a few microseconds per tile, per-tile sums too dear) and
-// lists with fewer than kMinRoundsOnDemand items per block keep the even split.
+// lists with fewer than kMinRoundsOnDemand items per block keep the even split.  The kernels that
+// take one worker at a time (items of two tiles of one worker) gain from handing out everything
+// earlier: the stand-alone step on a 2.0 GB launch -3.4 %, while sweep 2 of 5..7 workers on
+// 1.5..2.2 GB launches loses 2..6 % that way.
 enum OnDemand { kEvenSplit, kOnDemand, kOnDemandReducing };
 constexpr int kMinRoundsOnDemand = 4;
 constexpr int kMinRoundsAllOnDemandReducing = 32;     // per-tile sums: only worth it on long lists
-constexpr double kAllOnDemandBytes = 1.5e9;           // about 0.25 ms of traffic
+constexpr double kAllOnDemandBytes = 2.2e9;           // about 0.4 ms of traffic
+constexpr double kAllOnDemandBytesWorkerItems = 1.5e9;
 
 // Items [0, returned value) of `count` are split evenly over `blocks` blocks, the rest handed out
 // on demand; returns count when nothing is.  bytes_per_item: what one item moves.
-inline long long evenly_split_items(long long count, int blocks, OnDemand policy, double bytes_per_item) {
+inline long long evenly_split_items(long long count, int blocks, OnDemand policy, double bytes_per_item,
+                                    double all_from_bytes = kAllOnDemandBytes) {
   if (policy == kEvenSplit || blocks <= 0) return count;
   const long long rounds = count / blocks;
   if (rounds < kMinRoundsOnDemand) return count;
-  const bool all = static_cast<double>(count) * bytes_per_item >= kAllOnDemandBytes &&
+  const bool all = static_cast<double>(count) * bytes_per_item >= all_from_bytes &&
                    (policy != kOnDemandReducing || rounds >= kMinRoundsAllOnDemandReducing);
   return all ? 0 : (rounds - (rounds + 1) / 2) * blocks;
 }
@@ -208,7 +213,8 @@ inline Walk make_walk(int nfull, int ntiles, int tile_elems, int gfull, int work
   const long long count = static_cast<long long>(worker_item_groups(nfull, tiles_per_item)) * workers_per_tile;
   w.nitems = static_cast<int>(count);
   w.nstatic = static_cast<int>(
-      evenly_split_items(count, gfull, policy, bytes_per_elem * tile_elems * tiles_per_item));
+      evenly_split_items(count, gfull, policy, bytes_per_elem * tile_elems * tiles_per_item,
+                         tiles_per_item > 1 ? kAllOnDemandBytesWorkerItems : kAllOnDemandBytes));
   w.sched = w.nstatic < count ? sched : nullptr;
   return w;
 }
