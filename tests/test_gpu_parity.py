@@ -298,17 +298,24 @@ def test_results_are_reproducible_bitwise():
     plan.close()
 
 
-def test_pointer_tables_can_change_between_calls():
-    spec = W.small_spec(M=2, seed=41)
+@pytest.mark.parametrize("M", [2, 17, 40])
+def test_pointer_tables_can_change_between_calls(M):
+    # every kernel family reads the tables its own way (M = 17 and 40 entry by entry inside the loop
+    # over the workers): a table that changed since the last launch must be seen by the next one
+    spec = W.small_spec(M=M, seed=41)
     inp = W.make_inputs(spec)
-    plan = dppf.Plan(2, spec.numel)
+    plan = dppf.Plan(M, spec.numel)
     ref_new, ref_r, _, _ = O.pull_push_round(np.stack(inp.x), f32(0.1), f32(0.01))
-    r = torch.zeros(2, device="cuda")
+    r = torch.zeros(M, device="cuda")
+    keep = []
     for _ in range(3):                       # fresh allocations every time -> new tables
         x = _dev_rows(inp, inp.x)
+        keep.append(x)                       # so that no allocation is handed out twice
         plan.pull_push_round(x, f32(0.1), f32(0.01), r_out=r)
         assert_params_close(download_rows(x), ref_new, inp.offsets, 0, "x")
         assert_rel(r.cpu().numpy(), ref_r, 1e-4, "r")
+    for x in keep[:-1]:                      # the earlier sets were updated once, not again
+        assert_params_close(download_rows(x), ref_new, inp.offsets, 0, "x of an earlier call")
     plan.close()
 
 
